@@ -1,0 +1,149 @@
+/*
+ * flashkm.h — C ABI of the MI355X (gfx950) exact Lloyd k-means iteration.
+ *
+ * One Lloyd iteration (Flash-KMeans paper, Section 3.1, Eq. 2-3) is
+ *     assignment  a_i = argmin_k || x_i - c_k ||^2
+ *     update      n_k = #{i : a_i = k},  s_k = sum_{a_i = k} x_i,  c_k <- s_k / n_k
+ * computed here as the paper's two kernels: a fused distance + online-argmin pass that
+ * never stores the N x K distance matrix (Section 4.1, Algorithm 2), and a sort-inverse
+ * update that argsorts the assignment vector and reduces contiguous cluster segments of
+ * gathered rows (Section 4.2, Algorithm 3), plus the chunked host-streamed variant of
+ * Section 4.3.
+ *
+ * Conventions shared by every entry point
+ *   - Row-major, contiguous arrays.  B independent instances are stacked on the leading
+ *     axis: X[B,N,d], C[B,K,d], assign[B,N], counts[B,K].
+ *   - "device" pointers are HIP device memory owned by the caller, 16-byte aligned.
+ *     The library never allocates or frees device memory; scratch space is the caller's
+ *     `ws` buffer of at least fk_workspace_bytes(...) bytes (256-byte aligned), whose
+ *     contents are undefined before and after a call.
+ *   - X is never written.
+ *   - Indices are 0-based int32 (the paper counts from 1).  Ties in the argmin go to the
+ *     lowest index among the scores the kernel computes (fp32); a cluster with no member
+ *     keeps its previous centroid.
+ *   - Inputs must be finite; for FK_F16 twice the largest centroid norm must stay finite
+ *     in fp32 (always true for fp16 data).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work on it and return without waiting, except fk_lloyd_ooc.
+ *   - Supported shapes: 1 <= K <= 65536, 1 <= N, B*N < 2^31, B >= 1,
+ *     d a multiple of 8 with 8 <= d <= 128.  Anything else returns FK_EUNSUPPORTED or
+ *     FK_EINVAL; there is no fallback path.
+ *   - Every function returns an fk_status; on failure fk_last_error() holds a message for
+ *     the calling thread.  Nothing throws or aborts.
+ */
+#ifndef FLASHKM_H
+#define FLASHKM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { FK_F32 = 0, FK_F16 = 1, FK_BF16 = 2 } fk_dtype;
+
+typedef enum {
+    FK_OK = 0,
+    FK_EINVAL = 1,       /* NULL / misaligned pointer, non-positive size, bad enum */
+    FK_EUNSUPPORTED = 2, /* a shape or dtype this build has no kernel for */
+    FK_EWORKSPACE = 3,   /* ws_bytes smaller than fk_workspace_bytes(...) */
+    FK_EHIP = 4          /* a HIP runtime call failed; see fk_last_error() */
+} fk_status;
+
+/* Message for the last failure on the calling thread (static storage, never NULL). */
+const char* fk_last_error(void);
+
+/* Device-workspace size in bytes that the in-core entry points below need for this
+ * problem shape; 0 if the shape is unsupported.  Host-only, touches no GPU state. */
+size_t fk_workspace_bytes(int B, int64_t N, int d, int K, fk_dtype t);
+
+/*
+ * Assignment stage (Eq. 2; Section 4.1, Algorithm 2).
+ *   X       device, [B,N,d] of dtype t
+ *   C       device, [B,K,d] of dtype t (the centroids as the kernel consumes them)
+ *   assign  device out, [B,N] int32
+ *   min_dist device out or NULL, [B,N] float: || x_i - c_{a_i} ||^2 as the kernel sees it
+ *           (norm expansion of Section 3.1, fp32, clamped at 0)
+ * fp16/bf16: the x.c contraction runs on MFMA with fp32 accumulation against
+ * -||c_k||^2/2, the running (max, index) pair stays in registers over all centroid tiles
+ * (the paper's online argmin, with the row-constant ||x||^2 dropped); fp32: plain fp32
+ * direct differences.  HBM traffic is X + C read once, assign written once.
+ */
+fk_status fk_assign(const void* X, const void* C, int32_t* assign, float* min_dist,
+                    int B, int64_t N, int d, int K, fk_dtype t,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Inverse mapping of Section 4.2 (Algorithm 3, first two lines): stable argsort of the
+ * assignment vector by cluster id.
+ *   assign      device, [B,N] int32 with values in [0,K)  (values outside are undefined
+ *               behaviour of the result, never of memory: they are clamped)
+ *   sorted_idx  device out, [B,N] int32: point indices grouped by cluster, ascending
+ *               inside a cluster
+ *   seg_offsets device out, [B,K+1] int32: cluster k owns sorted_idx[seg_offsets[k] ..
+ *               seg_offsets[k+1]); seg_offsets[K] = N.  (This replaces the paper's
+ *               sorted id sequence: K+1 offsets carry the same information.)
+ */
+fk_status fk_sort_inverse(const int32_t* assign, int32_t* sorted_idx, int32_t* seg_offsets,
+                          int B, int64_t N, int K,
+                          void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Centroid update stage (Eq. 3; Section 4.2, Algorithm 3): sort-inverse + segment-level
+ * reduction + normalisation.  No floating-point atomics: segment pieces are merged in a
+ * fixed order, so results are bit-reproducible.
+ *   X          device, [B,N,d] of dtype t
+ *   assign     device, [B,N] int32 in [0,K)
+ *   C_prev_f32 device, [B,K,d] float: rows kept for empty clusters
+ *   C_out_f32  device out, [B,K,d] float (may alias C_prev_f32)
+ *   C_out_lp   device out or NULL, [B,K,d] of dtype t: C_out_f32 rounded to nearest even
+ *   counts     device out, [B,K] int32
+ */
+fk_status fk_update(const void* X, const int32_t* assign, const float* C_prev_f32,
+                    float* C_out_f32, void* C_out_lp, int32_t* counts,
+                    int B, int64_t N, int d, int K, fk_dtype t,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * `iters` Lloyd iterations (assignment with the current centroids, then update), all
+ * enqueued on `stream` with no host synchronisation.
+ *   C_f32   device in/out, [B,K,d] float master centroids
+ *   C_lp    device out or NULL, [B,K,d] of dtype t: what the *next* assignment would
+ *           consume (C_f32 rounded to nearest even).  Each iteration's assignment uses
+ *           the rounding of the C_f32 it starts from.
+ *   assign, counts  device out: those of the last iteration
+ * iters == 0 is a no-op.
+ */
+fk_status fk_lloyd_iter(const void* X, float* C_f32, void* C_lp, int32_t* assign,
+                        int32_t* counts, int B, int64_t N, int d, int K, fk_dtype t,
+                        int iters, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Out-of-core Lloyd iterations (Section 4.3, chunked stream overlap), B = 1.
+ *   X_host     PINNED host memory, [N,d] of dtype t.  Chunks of `chunk_rows` rows are
+ *              copied with hipMemcpyAsync on a side stream owned by the call into two
+ *              device buffers carved from dev_ws while the previous chunk is assigned and
+ *              reduced on `stream`.
+ *   C_f32      device in/out, [K,d] float.  The centroids are frozen during an iteration:
+ *              sums and counts accumulate over the chunks, one normalisation per iteration
+ *              (same result as the in-core path up to fp32 summation order).
+ *   assign     device out or NULL, [N] int32 (last iteration)
+ *   counts     device out, [K] int32
+ *   chunk_rows rows per chunk; 0 = the largest that fits dev_ws_bytes
+ *   dev_ws     device, dev_ws_bytes bytes: the whole device footprint of the call besides
+ *              C_f32 / assign / counts.  fk_ooc_workspace_bytes gives the size needed for a
+ *              given chunk_rows.
+ * Blocks the calling thread until all iterations are done.
+ */
+fk_status fk_lloyd_ooc(const void* X_host, float* C_f32, int32_t* assign, int32_t* counts,
+                       int64_t N, int d, int K, fk_dtype t, int iters, int64_t chunk_rows,
+                       void* dev_ws, size_t dev_ws_bytes, void* stream);
+
+/* Device bytes fk_lloyd_ooc needs for `chunk_rows` rows per chunk; 0 if unsupported. */
+size_t fk_ooc_workspace_bytes(int64_t chunk_rows, int d, int K, fk_dtype t);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLASHKM_H */

@@ -1,0 +1,293 @@
+// C-ABI entry points of flashkm.h: argument checks, workspace carving, kernel sequencing.
+// The arithmetic lives in fk_assign.hip / fk_sort.hip / fk_update.hip.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "fk_common.h"
+
+namespace fk {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+fk_status hip_fail(hipError_t e, const char* what) {
+    set_error("HIP error %d (%s) in %s", (int)e, hipGetErrorString(e), what);
+    return FK_EHIP;
+}
+
+static int ceil_log2(int v) {
+    int b = 0;
+    while ((1 << b) < v) ++b;
+    return b;
+}
+
+bool make_geometry(int B, int64_t N, int d, int K, fk_dtype t, Geometry* g) {
+    if (B < 1 || N < 1 || K < 1 || K > 65536 || d < 8 || d > 128 || (d % 8) != 0) return false;
+    if (t != FK_F32 && t != FK_F16 && t != FK_BF16) return false;
+    if ((int64_t)B * N >= ((int64_t)1 << 31)) return false;
+    g->B = B; g->N = N; g->d = d; g->K = K; g->t = t;
+    g->dchunks = d <= 32 ? 2 : (d <= 64 ? 4 : 8);
+    g->ktiles = (int)cdiv(K, 32);
+    int nbmax;
+    if (K <= 2048) {
+        g->sort_passes = 1;
+        g->sort_bits = ceil_log2(K) < 1 ? 1 : ceil_log2(K);
+        g->pass_bits[0] = g->sort_bits;
+        g->pass_bits[1] = 0;
+        nbmax = K;
+    } else {
+        g->sort_passes = 2;
+        g->sort_bits = ceil_log2(K);
+        g->pass_bits[0] = g->sort_bits / 2;
+        g->pass_bits[1] = g->sort_bits - g->pass_bits[0];
+        nbmax = 1 << g->pass_bits[1];
+    }
+    int64_t T = 16 * (int64_t)nbmax;
+    if (T < cdiv(N, 512)) T = cdiv(N, 512);
+    if (T < 1024) T = 1024;
+    T = cdiv(T, 1024) * 1024;
+    g->sort_tile = (int)T;
+    g->sort_blocks = (int)cdiv(N, T);
+    int64_t R = cdiv(N, 8192);
+    if (R < 64) R = 64;
+    g->rows_per_item = (int)R;
+    g->max_items = N / R + K;
+    return true;
+}
+
+Workspace carve(const Geometry& g, void* base) {
+    Workspace w;
+    memset(&w, 0, sizeof(w));
+    size_t off = 0;
+    char* p = (char*)base;
+    auto take = [&](size_t bytes) -> void* {
+        void* r = p ? (void*)(p + off) : nullptr;
+        off += align_up(bytes, 256);
+        return r;
+    };
+    const size_t BN = (size_t)g.B * (size_t)g.N;
+    const int nbmax = g.sort_passes == 1 ? g.K : (1 << g.pass_bits[1]);
+    // sort buffers first: their placement depends on (B, N, K) only
+    w.sorted_idx = (int32_t*)take(BN * 4);
+    w.seg_off = (int32_t*)take((size_t)g.B * (g.K + 1) * 4);
+    w.item_off = (int32_t*)take((size_t)g.B * (g.K + 1) * 4);
+    w.block_hist = (int32_t*)take((size_t)g.B * g.sort_blocks * nbmax * 4);
+    w.digit_off = (int32_t*)take((size_t)g.B * 2049 * 4);
+    if (g.sort_passes == 2) {
+        w.keys_tmp = (int32_t*)take(BN * 4);
+        w.vals_tmp = (int32_t*)take(BN * 4);
+        w.keys_sorted = (int32_t*)take(BN * 4);
+    }
+    const size_t sort_end = off;
+    (void)sort_end;
+    // shape/dtype dependent part
+    const size_t BKd = (size_t)g.B * g.K * g.d;
+    w.c_lp = take(BKd * elem_size(g.t));
+    if (g.t != FK_F32) {
+        w.c_frag = take((size_t)g.B * g.ktiles * g.dchunks * 64 * 16);
+        w.c_bias = (float*)take((size_t)g.B * g.ktiles * 32 * 4);
+    }
+    w.partial = (float*)take((size_t)g.B * (size_t)g.max_items * g.d * 4);
+    w.sums = (float*)take(BKd * 4);
+    w.bytes = off;
+    return w;
+}
+
+static size_t sort_workspace_bytes(const Geometry& g) {
+    const size_t BN = (size_t)g.B * (size_t)g.N;
+    const int nbmax = g.sort_passes == 1 ? g.K : (1 << g.pass_bits[1]);
+    size_t off = 0;
+    off += align_up(BN * 4, 256);
+    off += 2 * align_up((size_t)g.B * (g.K + 1) * 4, 256);
+    off += align_up((size_t)g.B * g.sort_blocks * nbmax * 4, 256);
+    off += align_up((size_t)g.B * 2049 * 4, 256);
+    if (g.sort_passes == 2) off += 3 * align_up(BN * 4, 256);
+    return off;
+}
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+static fk_status check_common(const char* fn, int B, int64_t N, int d, int K, fk_dtype t,
+                              const void* ws, size_t ws_bytes, Geometry* g) {
+    if (B < 1 || N < 1 || K < 1 || d < 1) {
+        set_error("%s: B, N, d, K must be positive (B=%d N=%lld d=%d K=%d)", fn, B, (long long)N, d, K);
+        return FK_EINVAL;
+    }
+    if (t != FK_F32 && t != FK_F16 && t != FK_BF16) {
+        set_error("%s: unknown dtype %d", fn, (int)t);
+        return FK_EINVAL;
+    }
+    if (!make_geometry(B, N, d, K, t, g)) {
+        set_error("%s: unsupported shape B=%d N=%lld d=%d K=%d (need d%%8==0, 8<=d<=128, K<=65536, B*N<2^31)",
+                  fn, B, (long long)N, d, K);
+        return FK_EUNSUPPORTED;
+    }
+    if (!ws || ((uintptr_t)ws & 255u)) {
+        set_error("%s: workspace pointer is NULL or not 256-byte aligned", fn);
+        return FK_EINVAL;
+    }
+    const size_t need = carve(*g, nullptr).bytes;
+    if (ws_bytes < need) {
+        set_error("%s: workspace too small: %zu bytes given, %zu needed", fn, ws_bytes, need);
+        return FK_EWORKSPACE;
+    }
+    return FK_OK;
+}
+
+#define FK_REQUIRE_PTR(fn, p)                                                      \
+    do {                                                                           \
+        if (!(p) || !fk::aligned16(p)) {                                           \
+            fk::set_error("%s: %s is NULL or not 16-byte aligned", fn, #p);        \
+            return FK_EINVAL;                                                      \
+        }                                                                          \
+    } while (0)
+#define FK_OPTIONAL_PTR(fn, p)                                                     \
+    do {                                                                           \
+        if ((p) && !fk::aligned16(p)) {                                            \
+            fk::set_error("%s: %s is not 16-byte aligned", fn, #p);                \
+            return FK_EINVAL;                                                      \
+        }                                                                          \
+    } while (0)
+#define FK_TRY(expr)                       \
+    do {                                   \
+        fk_status _s = (expr);             \
+        if (_s != FK_OK) return _s;        \
+    } while (0)
+
+// update = sort-inverse + segment reduce + merge/normalise, all into the carved workspace
+static fk_status run_update(const Geometry& g, const Workspace& w, const void* X,
+                            const int32_t* assign, const FinalizeArgs& fa, hipStream_t s) {
+    FK_TRY(launch_sort_inverse(g, w, assign, w.sorted_idx, w.seg_off, w.item_off, s));
+    FK_TRY(launch_segment_reduce(g, w, X, w.sorted_idx, w.seg_off, w.item_off, s));
+    FK_TRY(launch_finalize(g, w, w.seg_off, w.item_off, fa, s));
+    return FK_OK;
+}
+
+}  // namespace fk
+
+using namespace fk;
+
+extern "C" {
+
+const char* fk_last_error(void) { return fk::g_err; }
+
+size_t fk_workspace_bytes(int B, int64_t N, int d, int K, fk_dtype t) {
+    Geometry g;
+    if (!make_geometry(B, N, d, K, t, &g)) return 0;
+    return carve(g, nullptr).bytes;
+}
+
+fk_status fk_assign(const void* X, const void* C, int32_t* assign, float* min_dist, int B,
+                    int64_t N, int d, int K, fk_dtype t, void* ws, size_t ws_bytes,
+                    void* stream) {
+    Geometry g;
+    FK_TRY(check_common("fk_assign", B, N, d, K, t, ws, ws_bytes, &g));
+    FK_REQUIRE_PTR("fk_assign", X);
+    FK_REQUIRE_PTR("fk_assign", C);
+    FK_REQUIRE_PTR("fk_assign", assign);
+    FK_OPTIONAL_PTR("fk_assign", min_dist);
+    hipStream_t s = (hipStream_t)stream;
+    const Workspace w = carve(g, ws);
+    if (t == FK_F32) return launch_assign(g, X, C, nullptr, assign, min_dist, s);
+    FK_TRY(launch_prepare_centroids(g, C, w.c_frag, w.c_bias, s));
+    return launch_assign(g, X, w.c_frag, w.c_bias, assign, min_dist, s);
+}
+
+fk_status fk_sort_inverse(const int32_t* assign, int32_t* sorted_idx, int32_t* seg_offsets,
+                          int B, int64_t N, int K, void* ws, size_t ws_bytes, void* stream) {
+    Geometry g;
+    if (B < 1 || N < 1 || K < 1) {
+        set_error("fk_sort_inverse: B, N, K must be positive");
+        return FK_EINVAL;
+    }
+    if (!make_geometry(B, N, 8, K, FK_F32, &g)) {
+        set_error("fk_sort_inverse: unsupported shape B=%d N=%lld K=%d", B, (long long)N, K);
+        return FK_EUNSUPPORTED;
+    }
+    if (!ws || ((uintptr_t)ws & 255u)) {
+        set_error("fk_sort_inverse: workspace pointer is NULL or not 256-byte aligned");
+        return FK_EINVAL;
+    }
+    if (ws_bytes < sort_workspace_bytes(g)) {
+        set_error("fk_sort_inverse: workspace too small: %zu bytes given, %zu needed", ws_bytes,
+                  sort_workspace_bytes(g));
+        return FK_EWORKSPACE;
+    }
+    FK_REQUIRE_PTR("fk_sort_inverse", assign);
+    FK_REQUIRE_PTR("fk_sort_inverse", sorted_idx);
+    FK_REQUIRE_PTR("fk_sort_inverse", seg_offsets);
+    const Workspace w = carve(g, ws);
+    return launch_sort_inverse(g, w, assign, sorted_idx, seg_offsets, nullptr, (hipStream_t)stream);
+}
+
+fk_status fk_update(const void* X, const int32_t* assign, const float* C_prev_f32,
+                    float* C_out_f32, void* C_out_lp, int32_t* counts, int B, int64_t N, int d,
+                    int K, fk_dtype t, void* ws, size_t ws_bytes, void* stream) {
+    Geometry g;
+    FK_TRY(check_common("fk_update", B, N, d, K, t, ws, ws_bytes, &g));
+    FK_REQUIRE_PTR("fk_update", X);
+    FK_REQUIRE_PTR("fk_update", assign);
+    FK_REQUIRE_PTR("fk_update", C_prev_f32);
+    FK_REQUIRE_PTR("fk_update", C_out_f32);
+    FK_OPTIONAL_PTR("fk_update", C_out_lp);
+    FK_REQUIRE_PTR("fk_update", counts);
+    const Workspace w = carve(g, ws);
+    FinalizeArgs fa;
+    fa.C_prev_f32 = C_prev_f32;
+    fa.C_out_f32 = C_out_f32;
+    fa.C_out_lp = C_out_lp;
+    fa.counts = counts;
+    fa.sums = nullptr;
+    fa.accumulate = false;
+    fa.normalise = true;
+    return run_update(g, w, X, assign, fa, (hipStream_t)stream);
+}
+
+fk_status fk_lloyd_iter(const void* X, float* C_f32, void* C_lp, int32_t* assign,
+                        int32_t* counts, int B, int64_t N, int d, int K, fk_dtype t, int iters,
+                        void* ws, size_t ws_bytes, void* stream) {
+    Geometry g;
+    FK_TRY(check_common("fk_lloyd_iter", B, N, d, K, t, ws, ws_bytes, &g));
+    if (iters < 0) {
+        set_error("fk_lloyd_iter: iters must be >= 0");
+        return FK_EINVAL;
+    }
+    FK_REQUIRE_PTR("fk_lloyd_iter", X);
+    FK_REQUIRE_PTR("fk_lloyd_iter", C_f32);
+    FK_OPTIONAL_PTR("fk_lloyd_iter", C_lp);
+    FK_REQUIRE_PTR("fk_lloyd_iter", assign);
+    FK_REQUIRE_PTR("fk_lloyd_iter", counts);
+    if (iters == 0) return FK_OK;
+    hipStream_t s = (hipStream_t)stream;
+    const Workspace w = carve(g, ws);
+    void* lp = C_lp ? C_lp : w.c_lp;
+    // what the first assignment consumes: the master rounded to the storage type
+    FK_TRY(launch_round_centroids(g, C_f32, t == FK_F32 ? nullptr : lp, w.c_frag, w.c_bias, s));
+    for (int it = 0; it < iters; ++it) {
+        if (t == FK_F32)
+            FK_TRY(launch_assign(g, X, C_f32, nullptr, assign, nullptr, s));
+        else
+            FK_TRY(launch_assign(g, X, w.c_frag, w.c_bias, assign, nullptr, s));
+        FinalizeArgs fa;
+        fa.C_prev_f32 = C_f32;
+        fa.C_out_f32 = C_f32;
+        fa.C_out_lp = (t == FK_F32) ? (it + 1 == iters ? C_lp : nullptr) : lp;
+        fa.counts = counts;
+        fa.sums = nullptr;
+        fa.accumulate = false;
+        fa.normalise = true;
+        FK_TRY(run_update(g, w, X, assign, fa, s));
+        if (t != FK_F32 && it + 1 < iters)
+            FK_TRY(launch_prepare_centroids(g, lp, w.c_frag, w.c_bias, s));
+    }
+    return FK_OK;
+}
+
+}  // extern "C"

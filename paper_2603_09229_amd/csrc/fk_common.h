@@ -1,0 +1,111 @@
+// Internal declarations shared by the flashkm translation units (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "flashkm.h"
+
+namespace fk {
+
+// ---------------------------------------------------------------- errors
+void set_error(const char* fmt, ...);
+fk_status hip_fail(hipError_t e, const char* what);
+
+#define FK_HIP(call)                                           \
+    do {                                                       \
+        hipError_t _e = (call);                                \
+        if (_e != hipSuccess) return fk::hip_fail(_e, #call);  \
+    } while (0)
+
+// ---------------------------------------------------------------- small helpers
+constexpr int kWave = 64;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t elem_size(fk_dtype t) { return t == FK_F32 ? 4 : 2; }
+
+// ---------------------------------------------------------------- problem geometry
+//
+// Centroids for the MFMA path are kept in "fragment order": centroid tile (32 rows) x
+// feature chunk (16 features) x lane (64) x 8 elements, so that a 32x32x16 MFMA A-operand
+// is one 16-byte LDS read per lane at lane*16.  Rows beyond K and features beyond d are
+// zero; their score bias is -inf so they never win.
+struct Geometry {
+    int B;
+    int64_t N;        // points per instance
+    int d, K;
+    fk_dtype t;
+    int dchunks;      // ceil(d / 16)
+    int ktiles;       // ceil(K / 32)
+    // counting sort
+    int sort_bits;    // bits of a cluster id, ceil(log2 K), >= 1
+    int sort_passes;  // 1 when K <= 2048, else 2
+    int pass_bits[2];
+    int sort_tile;    // keys per sort workgroup
+    int sort_blocks;  // workgroups per instance = ceil(N / sort_tile)
+    // segment reduction
+    int rows_per_item;   // R: sorted positions one wave reduces
+    int64_t max_items;   // upper bound on sum_k ceil(n_k / R) per instance
+};
+
+// Carved device workspace (all pointers 256-byte aligned inside the caller's buffer).
+struct Workspace {
+    void* c_lp;          // [B,K,d] low-precision centroids consumed by assign (lloyd only)
+    void* c_frag;        // [B,ktiles,dchunks,64,8] fragment-ordered centroids (16-bit types)
+    float* c_bias;       // [B,ktiles*32] -||c||^2/2, -inf for padding rows
+    int32_t* sorted_idx; // [B,N]
+    int32_t* seg_off;    // [B,K+1]
+    int32_t* item_off;   // [B,K+1] exclusive scan of ceil(n_k / R)
+    int32_t* block_hist; // [B,bins,sort_blocks] per-workgroup digit histograms
+    int32_t* digit_off;  // [B,2048+1] digit offsets of the current radix pass
+    int32_t* keys_tmp;   // [B,N] keys after pass 1 (two-pass sort only)
+    int32_t* vals_tmp;   // [B,N] values after pass 1 (two-pass sort only)
+    int32_t* keys_sorted;// [B,N] sorted keys (two-pass sort only)
+    float* partial;      // [B,max_items,d] per-item segment sums
+    float* sums;         // [B,K,d] accumulated sums (chunked mode)
+    size_t bytes;        // total bytes carved
+};
+
+bool make_geometry(int B, int64_t N, int d, int K, fk_dtype t, Geometry* g);
+// Lays the workspace out from `base` (may be NULL to only compute the size).
+Workspace carve(const Geometry& g, void* base);
+
+// ---------------------------------------------------------------- kernel launchers
+// Each enqueues on `s` and returns FK_OK / FK_EHIP.  Pointers are device pointers.
+
+// C (dtype t, [B,K,d]) -> fragment-ordered copy + score bias.  16-bit types only.
+fk_status launch_prepare_centroids(const Geometry& g, const void* C_lp, void* c_frag,
+                                   float* c_bias, hipStream_t s);
+// C_f32 -> C_lp (round to nearest even), and for 16-bit types also c_frag / c_bias.
+fk_status launch_round_centroids(const Geometry& g, const float* C_f32, void* C_lp,
+                                 void* c_frag, float* c_bias, hipStream_t s);
+// Fused distance + online argmin.  16-bit: reads c_frag/c_bias; fp32: reads C directly.
+fk_status launch_assign(const Geometry& g, const void* X, const void* C_or_frag,
+                        const float* c_bias, int32_t* assign, float* min_dist, hipStream_t s);
+// Stable argsort by cluster id -> sorted_idx, seg_off (+ item_off when w.item_off != NULL).
+fk_status launch_sort_inverse(const Geometry& g, const Workspace& w, const int32_t* assign,
+                              int32_t* sorted_idx, int32_t* seg_off, int32_t* item_off,
+                              hipStream_t s);
+// Per-item segment sums of gathered rows -> w.partial.
+fk_status launch_segment_reduce(const Geometry& g, const Workspace& w, const void* X,
+                                const int32_t* sorted_idx, const int32_t* seg_off,
+                                const int32_t* item_off, hipStream_t s);
+// Merge item sums per cluster; optionally accumulate into sums/counts; optionally
+// normalise and emit centroids (fp32 master, rounded copy, fragment copy, bias).
+struct FinalizeArgs {
+    const float* C_prev_f32;
+    float* C_out_f32;
+    void* C_out_lp;      // may be NULL
+    void* c_frag;        // may be NULL
+    float* c_bias;       // may be NULL
+    int32_t* counts;     // [B,K]
+    float* sums;         // [B,K,d] (needed when accumulate || !normalise)
+    bool accumulate;     // add onto sums / counts already there
+    bool normalise;      // divide and write centroids
+};
+fk_status launch_finalize(const Geometry& g, const Workspace& w, const int32_t* seg_off,
+                          const int32_t* item_off, const FinalizeArgs& a, hipStream_t s);
+
+}  // namespace fk

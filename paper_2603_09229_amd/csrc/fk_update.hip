@@ -1,0 +1,211 @@
+// Segment-level aggregation and normalisation of the sort-inverse update (paper Section
+// 4.2, Algorithm 3; Eq. 3).
+//
+// The paper cuts the sorted order into fixed chunks, accumulates each cluster-id segment
+// of a chunk on chip and merges it with one atomic_add per segment.  Here the cut follows
+// the segments instead: cluster k's run of n_k sorted positions is split into
+// ceil(n_k / R) "items" of at most R positions, one wave reduces one item in registers and
+// writes one partial row, and a second kernel adds a cluster's partial rows in item order.
+// That keeps the paper's bound on merges (at most K + N/R rows are merged) but needs no
+// atomics at all and is bit-reproducible.  X is gathered by whole rows through sorted_idx
+// and never permuted in memory.
+#include "fk_common.h"
+
+namespace fk {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+__device__ __forceinline__ float lp_to_float(uint16_t v, bool bf) {
+    return bf ? __uint_as_float((uint32_t)v << 16) : (float)__builtin_bit_cast(_Float16, v);
+}
+__device__ __forceinline__ uint16_t float_to_lp(float f, bool bf) {
+    if (bf) {
+        uint32_t u = __float_as_uint(f);
+        u += 0x7FFFu + ((u >> 16) & 1u);
+        return (uint16_t)(u >> 16);
+    }
+    return __builtin_bit_cast(uint16_t, (_Float16)f);
+}
+
+// Largest k in [0,K) with item_off[k] <= item, found by the whole wave 64 probes at a
+// time.  Requires item < item_off[K]; the cluster found is then non-empty.
+__device__ __forceinline__ int find_cluster(const int32_t* __restrict__ item_off, int K,
+                                            int item, int lane) {
+    int lo = 0, hi = K;
+    while (hi - lo > 1) {
+        const int step = (hi - lo + 63) >> 6;
+        const int probe = lo + lane * step;
+        const bool le = probe < hi && item_off[probe] <= item;
+        const int cnt = __popcll(__ballot(le));   // monotone: a prefix of the lanes
+        lo += (cnt - 1) * step;
+        hi = min(hi, lo + step);
+    }
+    return lo;
+}
+
+}  // namespace
+
+// One wave per item.  EPL elements of 16 bytes per lane (8 for 16-bit types, 4 for fp32);
+// 2^lpr_log2 lanes span a row, so a wave reads 64 >> lpr_log2 rows per load instruction.
+template <int EPL, bool BF>
+__global__ __launch_bounds__(256) void segment_reduce_kernel(
+    const void* __restrict__ Xv, const int32_t* __restrict__ sorted_idx,
+    const int32_t* __restrict__ seg_off, const int32_t* __restrict__ item_off,
+    float* __restrict__ partial, int64_t N, int d, int K, int R, int64_t max_items,
+    int lpr_log2) {
+    const int b = blockIdx.y;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t item = (int64_t)blockIdx.x * 4 + wave;
+    seg_off += (size_t)b * (K + 1);
+    item_off += (size_t)b * (K + 1);
+    sorted_idx += (size_t)b * N;
+    if (item >= item_off[K]) return;   // wave-uniform
+    const int k = find_cluster(item_off, K, (int)item, lane);
+    const int piece = (int)item - item_off[k];
+    const int start = seg_off[k] + piece * R;
+    const int end = min(seg_off[k + 1], start + R);
+
+    const int LPR = 1 << lpr_log2, S = 64 >> lpr_log2;
+    const int slot = lane >> lpr_log2, col = (lane & (LPR - 1)) * EPL;
+    const bool active = col < d;
+    const char* X = (const char*)Xv + (size_t)b * N * d * (16 / EPL);
+    float acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+
+    constexpr int U = 4;
+    for (int r0 = start; r0 < end; r0 += 64) {
+        const int nrows = min(64, end - r0);
+        const int myidx = lane < nrows ? sorted_idx[r0 + lane] : 0;
+        for (int q = 0; q < nrows; q += S * U) {
+            uintx4 v[U];
+            bool ok[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int rr = q + u * S + slot;              // < 64 always
+                const int idx = __shfl(myidx, rr);
+                ok[u] = active && rr < nrows;
+                v[u] = uintx4{0u, 0u, 0u, 0u};
+                if (ok[u]) v[u] = *(const uintx4*)(X + ((size_t)idx * d + col) * (16 / EPL));
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (EPL == 4) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[e] += __uint_as_float(v[u][e]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        acc[2 * e] += lp_to_float((uint16_t)(v[u][e] & 0xFFFFu), BF);
+                        acc[2 * e + 1] += lp_to_float((uint16_t)(v[u][e] >> 16), BF);
+                    }
+                }
+            }
+        }
+    }
+    // add the row slots of the wave together (fixed butterfly order)
+    for (int o = LPR; o < 64; o <<= 1) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], o);
+    }
+    if (slot == 0 && active) {
+        float* out = partial + ((size_t)b * max_items + item) * d + col;
+#pragma unroll
+        for (int e = 0; e < EPL; e += 4)
+            *(floatx4*)(out + e) = floatx4{acc[e], acc[e + 1], acc[e + 2], acc[e + 3]};
+    }
+}
+
+// One workgroup per cluster: s_k = sum of the cluster's item rows in item order,
+// n_k = seg_off[k+1] - seg_off[k].  Optionally added onto sums/counts already stored
+// (chunked mode), optionally normalised into centroids (Algorithm 3, last loop; an empty
+// cluster keeps its previous centroid).
+__global__ __launch_bounds__(256) void finalize_kernel(
+    const float* __restrict__ partial, const int32_t* __restrict__ seg_off,
+    const int32_t* __restrict__ item_off, const float* C_prev,
+    float* C_out, uint16_t* __restrict__ C_lp_out, float* __restrict__ C_lp_f32_out,
+    int32_t* __restrict__ counts, float* __restrict__ sums, int d, int K, int64_t max_items,
+    int accumulate, int normalise, int bf) {
+    __shared__ float red[256];
+    const int b = blockIdx.y, k = blockIdx.x;
+    seg_off += (size_t)b * (K + 1);
+    item_off += (size_t)b * (K + 1);
+    const int T = blockDim.x;
+    // d <= 128 <= T: thread = (row slot, feature)
+    int dpow = 1;
+    while (dpow < d) dpow <<= 1;
+    const int slots = T / dpow, slot = threadIdx.x / dpow, j = threadIdx.x % dpow;
+    const int i0 = item_off[k], i1 = item_off[k + 1];
+    // read the running count before anyone overwrites it (barrier below)
+    const int n_prev = accumulate ? counts[(size_t)b * K + k] : 0;
+    const float* P = partial + (size_t)b * max_items * d;
+    float acc = 0.f;
+    if (j < d && slot < slots)
+        for (int it = i0 + slot; it < i1; it += slots) acc += P[(size_t)it * d + j];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (threadIdx.x < d) {
+        float s = 0.f;
+        for (int q = 0; q < slots; ++q) s += red[q * dpow + threadIdx.x];   // fixed order
+        const size_t o = ((size_t)b * K + k) * d + threadIdx.x;
+        const int n = seg_off[k + 1] - seg_off[k] + n_prev;
+        if (accumulate) s += sums[o];
+        if (sums) sums[o] = s;
+        if (normalise) {
+            const float c = n > 0 ? (float)((double)s / (double)n) : C_prev[o];
+            C_out[o] = c;
+            if (C_lp_out) C_lp_out[o] = float_to_lp(c, bf);
+            if (C_lp_f32_out) C_lp_f32_out[o] = c;
+        }
+        if (threadIdx.x == 0) counts[(size_t)b * K + k] = n;
+    }
+}
+
+// ------------------------------------------------------------------------------------
+static int ceil_log2(int v) {
+    int b = 0;
+    while ((1 << b) < v) ++b;
+    return b;
+}
+
+fk_status launch_segment_reduce(const Geometry& g, const Workspace& w, const void* X,
+                                const int32_t* sorted_idx, const int32_t* seg_off,
+                                const int32_t* item_off, hipStream_t s) {
+    const int epl = g.t == FK_F32 ? 4 : 8;
+    const int lpr_log2 = ceil_log2((int)cdiv(g.d, epl));
+    dim3 grid((unsigned)cdiv(g.max_items, 4), g.B), block(256);
+    if (g.t == FK_F32)
+        hipLaunchKernelGGL((segment_reduce_kernel<4, false>), grid, block, 0, s, X, sorted_idx,
+                           seg_off, item_off, w.partial, g.N, g.d, g.K, g.rows_per_item,
+                           g.max_items, lpr_log2);
+    else if (g.t == FK_F16)
+        hipLaunchKernelGGL((segment_reduce_kernel<8, false>), grid, block, 0, s, X, sorted_idx,
+                           seg_off, item_off, w.partial, g.N, g.d, g.K, g.rows_per_item,
+                           g.max_items, lpr_log2);
+    else
+        hipLaunchKernelGGL((segment_reduce_kernel<8, true>), grid, block, 0, s, X, sorted_idx,
+                           seg_off, item_off, w.partial, g.N, g.d, g.K, g.rows_per_item,
+                           g.max_items, lpr_log2);
+    FK_HIP(hipGetLastError());
+    return FK_OK;
+}
+
+fk_status launch_finalize(const Geometry& g, const Workspace& w, const int32_t* seg_off,
+                          const int32_t* item_off, const FinalizeArgs& a, hipStream_t s) {
+    // few large clusters: more row slots per workgroup
+    const int threads = (g.max_items / g.K >= 8) ? 256 : 128;
+    uint16_t* lp16 = g.t == FK_F32 ? nullptr : (uint16_t*)a.C_out_lp;
+    float* lp32 = g.t == FK_F32 ? (float*)a.C_out_lp : nullptr;
+    if (lp32 == a.C_out_f32) lp32 = nullptr;
+    hipLaunchKernelGGL(finalize_kernel, dim3(g.K, g.B), dim3(threads), 0, s, w.partial, seg_off,
+                       item_off, a.C_prev_f32, a.C_out_f32, lp16, lp32, a.counts, a.sums, g.d, g.K,
+                       g.max_items, a.accumulate ? 1 : 0, a.normalise ? 1 : 0,
+                       g.t == FK_BF16 ? 1 : 0);
+    FK_HIP(hipGetLastError());
+    return FK_OK;
+}
+
+}  // namespace fk

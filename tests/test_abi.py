@@ -1,0 +1,74 @@
+"""CPU-side checks of the boundary: the library loads without a GPU, exports every symbol the
+header declares, and its host-only logic (workspace sizing, argument validation, which all
+happens before the first HIP call) behaves.  No kernel is launched here."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+import torch
+
+from paper_2603_09229_amd import binding as fk
+
+ROOT = Path(__file__).resolve().parent.parent
+HEADER = ROOT / "include" / "flashkm.h"
+
+
+def _declared():
+    text = re.sub(r"/\*.*?\*/", "", HEADER.read_text(), flags=re.S)
+    return sorted(set(re.findall(r"\b(fk_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_all_exported():
+    names = _declared()
+    assert set(names) == set(fk.EXPORTS)
+    L = fk.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_workspace_sizes_are_sane():
+    f16, f32 = torch.float16, torch.float32
+    base = fk.fk_workspace_bytes(1, 1 << 20, 128, 1024, f16)
+    assert base >= (1 << 20) * 4                            # at least sorted_idx
+    assert base < (1 << 20) * 128 * 2                       # and well below one copy of X
+    assert fk.fk_workspace_bytes(2, 1 << 20, 128, 1024, f16) > base
+    assert fk.fk_workspace_bytes(1, 1 << 20, 128, 65536, f16) > base
+    assert fk.fk_workspace_bytes(1, 1000, 64, 10, f32) % 256 == 0
+    for bad in [(0, 10, 64, 4), (1, 0, 64, 4), (1, 10, 12, 4), (1, 10, 136, 4), (1, 10, 64, 0),
+                (1, 10, 64, 65537), (3, 1 << 30, 64, 4)]:
+        assert fk.fk_workspace_bytes(*bad, f16) == 0
+    assert fk.fk_ooc_workspace_bytes(1 << 16, 128, 65536, f16) > 2 * (1 << 16) * 256
+    assert fk.fk_ooc_workspace_bytes(0, 128, 16, f16) == 0
+
+
+def test_argument_validation_happens_on_the_host():
+    L = fk.lib()
+    buf = ctypes.create_string_buffer(1 << 16)
+    p = ctypes.c_void_p((ctypes.addressof(buf) + 255) & ~255)
+    # NULL data pointers -> FK_EINVAL, before any GPU call
+    rc = L.fk_assign(None, None, None, None, 1, 16, 16, 2, fk.FK_F16, p, 1 << 15, None)
+    assert rc == 1 and b"NULL" in L.fk_last_error()
+    # unsupported shape
+    rc = L.fk_assign(p, p, p, None, 1, 16, 20, 2, fk.FK_F16, p, 1 << 15, None)
+    assert rc == 2
+    # workspace too small
+    rc = L.fk_update(p, p, p, p, None, p, 1, 1 << 20, 128, 1024, fk.FK_F16, p, 1024, None)
+    assert rc == 3 and b"workspace too small" in L.fk_last_error()
+    # bad dtype enum
+    rc = L.fk_lloyd_iter(p, p, None, p, p, 1, 16, 16, 2, 7, 1, p, 1 << 15, None)
+    assert rc == 1
+    rc = L.fk_lloyd_iter(p, p, None, p, p, 1, 16, 16, 2, fk.FK_F16, -1, p, 1 << 15, None)
+    assert rc == 1
+    # iters == 0 is a no-op that touches nothing
+    assert L.fk_lloyd_iter(p, p, None, p, p, 1, 16, 16, 2, fk.FK_F16, 0, p, 1 << 15, None) == 0
+    rc = L.fk_sort_inverse(p, p, p, 1, 100, 70000, p, 1 << 15, None)
+    assert rc == 2
+    rc = L.fk_lloyd_ooc(None, p, None, p, 100, 16, 4, fk.FK_F16, 1, 0, p, 1 << 15, None)
+    assert rc == 1
+
+
+def test_binding_rejects_host_tensors():
+    X = torch.zeros((1, 8, 16), dtype=torch.float16)
+    with pytest.raises(ValueError):
+        fk.fk_assign(X, X[:, :2], ws=torch.empty(1024, dtype=torch.uint8))

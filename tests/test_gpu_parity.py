@@ -1,0 +1,256 @@
+"""GPU parity: every C-ABI entry point against the fp64 oracle on the same seeded inputs.
+
+Sizes are small enough for the oracle to finish in seconds but span several point tiles,
+several centroid tiles, ragged tails in N, K and d, and more than one batch instance.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_09229_amd import binding as fk
+from paper_2603_09229_amd import workloads as wl
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _problem(dtype, B, N, d, K, seed, center_std=4.0, noise=1.0, zipf=0.0):
+    name = {torch.float32: "fp32", torch.float16: "fp16", torch.bfloat16: "bf16"}[dtype]
+    w = wl.Workload("t", B, N, d, K, name, center_std, noise, zipf, 1, seed)
+    X, lab = wl.make_points(w, return_labels=True)
+    idx = wl.init_rows(w) if K <= N else torch.randint(0, N, (B, K))
+    C0 = wl.gather_rows(X, idx)            # float32, exact stored rows
+    return w, X, lab, C0
+
+
+ASSIGN_CASES = [
+    # dtype, B, N, d, K
+    (torch.float16, 1, 5000, 128, 1000),     # ragged N and K tiles, several LDS stages
+    (torch.float16, 1, 4099, 64, 16),        # K smaller than one centroid tile
+    (torch.bfloat16, 3, 2500, 128, 256),     # batched
+    (torch.float16, 2, 700, 32, 70),
+    (torch.float16, 1, 513, 8, 5),           # smallest d
+    (torch.bfloat16, 1, 1000, 96, 33),       # d not a power of two (zero-padded chunks)
+    (torch.float16, 1, 300, 24, 40),         # d = 8 mod 16
+    (torch.float16, 1, 1, 128, 1),           # degenerate: one point, one centroid
+    (torch.float16, 1, 64, 128, 2500),       # K > N, two sort passes later on
+    (torch.float32, 1, 3000, 64, 64),
+    (torch.float32, 2, 777, 8, 3),
+    (torch.float32, 1, 500, 128, 130),
+    (torch.float32, 1, 400, 40, 7),
+]
+
+
+@pytest.mark.parametrize("dtype,B,N,d,K", ASSIGN_CASES)
+def test_assign_matches_oracle(dtype, B, N, d, K):
+    w, X, _, C0 = _problem(dtype, B, N, d, K, seed=100 + N + K)
+    C = C0.to(dtype)                                   # what the kernel consumes
+    a, md = fk.fk_assign(X.to(DEV), C.to(DEV), min_dist=True)
+    torch.cuda.synchronize()
+    a, md = a.cpu().numpy(), md.cpu().numpy()
+    for b in range(B):
+        Xb, Cb = parity.widen(X[b]), parity.widen(C[b])
+        ref = oracle.assign(Xb, Cb)
+        st = parity.check_assign(Xb, Cb, a[b], ref)
+        assert st["mismatch"] <= max(2, N // 50), st     # near-ties are rare on these mixtures
+        same = a[b] == ref["assign"]
+        scale = ref["xnorm2"] + (Cb.astype(np.float64) ** 2).sum(1)[a[b]]
+        tol = (1e-3 if dtype != torch.float32 else 1e-5) * scale + 1e-6
+        assert (np.abs(md[b][same] - ref["best"][same]) <= tol[same]).all()
+
+
+def test_assign_exact_duplicates_go_to_lowest_index():
+    w, X, _, C0 = _problem(torch.float16, 1, 2000, 128, 96, seed=7)
+    C = C0.to(torch.float16)
+    C[0, 70] = C[0, 3]          # same tile column, other half-wave
+    C[0, 40] = C[0, 39]         # neighbours
+    C[0, 95] = C[0, 0]          # different centroid tiles
+    a = fk.fk_assign(X.to(DEV), C.to(DEV)).cpu().numpy()[0]
+    assert not np.isin(a, [70, 40, 95]).any()
+    parity.check_assign(parity.widen(X[0]), parity.widen(C[0]), a)
+
+
+def test_assign_does_not_depend_on_tiling_position():
+    """Online argmin: shifting where a point falls in a tile must not change its answer."""
+    w, X, _, C0 = _problem(torch.float16, 1, 1500, 64, 200, seed=9)
+    C = C0.to(torch.float16).to(DEV)
+    a_full = fk.fk_assign(X.to(DEV), C).cpu()
+    off = 37
+    a_shift = fk.fk_assign(X[:, off:].contiguous().to(DEV), C).cpu()
+    assert torch.equal(a_full[:, off:], a_shift)
+
+
+SORT_CASES = [(1, 5000, 1), (2, 4097, 16), (1, 100000, 1000), (1, 33333, 2048), (1, 70001, 2049),
+              (2, 50000, 5000), (1, 200000, 65536), (1, 1, 5), (1, 300000, 16)]
+
+
+@pytest.mark.parametrize("B,N,K", SORT_CASES)
+def test_sort_inverse_is_the_stable_argsort(B, N, K):
+    g = torch.Generator().manual_seed(N + K)
+    p = wl.membership_probs(K, 1.2 if K <= 64 else 0.0)
+    a = torch.multinomial(p.float(), B * N, replacement=True, generator=g).view(B, N).to(torch.int32)
+    if K > 3:
+        a[a == 2] = 1                                    # an empty cluster in the middle
+    si, so = fk.fk_sort_inverse(a.to(DEV), K)
+    si, so = si.cpu().numpy(), so.cpu().numpy()
+    for b in range(B):
+        ab = a[b].numpy()
+        assert (si[b] == np.argsort(ab, kind="stable")).all()
+        ref_off = np.concatenate([[0], np.cumsum(np.bincount(ab, minlength=K))])
+        assert (so[b] == ref_off).all()
+
+
+def test_sort_inverse_single_cluster_and_sorted_input():
+    a = torch.zeros((1, 70000), dtype=torch.int32)
+    si, so = fk.fk_sort_inverse(a.to(DEV), 8)
+    assert torch.equal(si.cpu()[0], torch.arange(70000, dtype=torch.int32))
+    assert so.cpu()[0].tolist() == [0] + [70000] * 8
+    a = torch.arange(3000, dtype=torch.int32).view(1, -1)
+    si, so = fk.fk_sort_inverse(a.to(DEV), 3000)
+    assert torch.equal(si.cpu()[0], torch.arange(3000, dtype=torch.int32))
+
+
+UPDATE_CASES = [
+    (torch.float16, 1, 20000, 128, 300, 0.0),
+    (torch.float16, 1, 100000, 64, 16, 1.2),      # skewed: many items per cluster
+    (torch.bfloat16, 2, 6000, 128, 256, 0.0),
+    (torch.float32, 1, 16384, 64, 64, 0.0),
+    (torch.float32, 1, 3000, 128, 10, 0.0),
+    (torch.float16, 1, 900, 24, 2500, 0.0),       # K > N: mostly empty clusters, 2-pass sort
+    (torch.float16, 1, 5000, 8, 3, 0.0),
+    (torch.bfloat16, 1, 4000, 96, 50, 0.0),
+]
+
+
+@pytest.mark.parametrize("dtype,B,N,d,K,zipf", UPDATE_CASES)
+def test_update_matches_oracle(dtype, B, N, d, K, zipf):
+    w, X, lab, C0 = _problem(dtype, B, N, d, K, seed=200 + N, zipf=zipf)
+    a = lab.clone()
+    if K > 4:
+        a[a == 1] = 0                                     # force one empty cluster
+    C_new, C_lp, counts = fk.fk_update(X.to(DEV), a.to(DEV), C0.to(DEV))
+    torch.cuda.synchronize()
+    assert torch.equal(C_lp.cpu(), C_new.cpu().to(dtype))          # rounding to nearest even
+    tol = parity.CENTROID_TOL[dtype]
+    for b in range(B):
+        parity.check_update(parity.widen(X[b]), a[b].numpy(), C0[b].numpy(),
+                            C_new[b].cpu().numpy(), counts[b].cpu().numpy(), tol)
+
+
+def test_update_is_bit_reproducible_and_leaves_x_alone():
+    w, X, lab, C0 = _problem(torch.float16, 1, 50000, 128, 64, seed=5)
+    Xd = X.to(DEV)
+    keep = Xd.clone()
+    r1 = fk.fk_update(Xd, lab.to(DEV), C0.to(DEV))
+    r2 = fk.fk_update(Xd, lab.to(DEV), C0.to(DEV))
+    assert torch.equal(r1[0], r2[0]) and torch.equal(r1[2], r2[2])
+    assert torch.equal(Xd, keep)
+
+
+def _teacher_forced(w, iters, zipf_init=False, max_mismatch_frac=0.02):
+    X, lab = wl.make_points(w, return_labels=True)
+    idx = wl.init_rows(w, lab if zipf_init else None)
+    C = wl.gather_rows(X, idx).to(DEV)                   # fp32 master on device
+    Xd = X.to(DEV)
+    dtype = w.torch_dtype
+    tol = parity.CENTROID_TOL[dtype]
+    ws = fk.make_workspace(w.B, w.N, w.d, w.K, dtype, DEV)
+    Xh = [parity.widen(X[b]) for b in range(w.B)]
+    prev_lp = None
+    J_prev = None
+    for it in range(iters):
+        C_before = C.clone()
+        consumed = C_before.to(dtype)                    # what this iteration's assign reads
+        if prev_lp is not None:
+            assert torch.equal(prev_lp, consumed)
+        a, counts, C_lp = fk.fk_lloyd_iter(Xd, C, 1, ws=ws)
+        torch.cuda.synchronize()
+        prev_lp = C_lp.clone()
+        a_h, cnt_h = a.cpu().numpy(), counts.cpu().numpy()
+        J = 0.0
+        for b in range(w.B):
+            Cb = parity.widen(consumed[b])
+            ref = oracle.assign(Xh[b], Cb)
+            st = parity.check_assign(Xh[b], Cb, a_h[b], ref)
+            assert st["mismatch"] <= max_mismatch_frac * w.N + 2, (it, b, st)
+            parity.check_update(Xh[b], a_h[b], C_before[b].cpu().numpy(), C[b].cpu().numpy(),
+                                cnt_h[b], tol)
+            J += oracle.inertia(Xh[b], C[b].cpu().numpy(), a_h[b])
+        if J_prev is not None:
+            assert J <= J_prev * (1 + 1e-3), (it, J, J_prev)      # Lloyd never goes uphill
+        J_prev = J
+
+
+def test_lloyd_c1_full_size_fp32():
+    _teacher_forced(wl.C1, wl.C1.iters)
+
+
+def test_lloyd_c2_recipe_scaled_fp16():
+    _teacher_forced(wl.C2.scaled(N=40000, K=1024), 4)
+
+
+def test_lloyd_c3_recipe_scaled_bf16_batched():
+    # overlapping clusters (centre spacing ~ noise): near-ties are common here by design
+    _teacher_forced(wl.C3.scaled(B=3, N=4096), 3, max_mismatch_frac=0.05)
+
+
+def test_lloyd_c4_recipe_scaled_skewed():
+    _teacher_forced(wl.C4.scaled(N=1 << 17), 3, zipf_init=True)
+
+
+def test_lloyd_multi_iteration_call_equals_repeated_single_calls():
+    w = wl.C2.scaled(N=20000, K=200)
+    X = wl.make_points(w).to(DEV)
+    C0 = wl.gather_rows(X.cpu(), wl.init_rows(w)).to(DEV)
+    Ca, Cb = C0.clone(), C0.clone()
+    a1, n1, lp1 = fk.fk_lloyd_iter(X, Ca, 5)
+    for _ in range(5):
+        a2, n2, lp2 = fk.fk_lloyd_iter(X, Cb, 1)
+    assert torch.equal(Ca, Cb) and torch.equal(a1, a2) and torch.equal(n1, n2) and torch.equal(lp1, lp2)
+
+
+@pytest.mark.parametrize("dtype,N,d,K,chunk", [
+    (torch.float16, 50000, 64, 300, 16384),       # ragged tail chunk
+    (torch.float16, 40000, 128, 3000, 8192),      # two-pass sort inside every chunk
+    (torch.float32, 20000, 32, 20, 20000),        # single chunk
+    (torch.bfloat16, 30000, 128, 64, 0),          # chunk size chosen from the workspace
+])
+def test_out_of_core_equals_in_core(dtype, N, d, K, chunk):
+    w, X, _, C0 = _problem(dtype, 1, N, d, K, seed=300 + N)
+    Xpin = X[0].clone().pin_memory()
+    rows = chunk if chunk else 12288
+    ws_bytes = fk.fk_ooc_workspace_bytes(rows, d, K, dtype)
+    assert ws_bytes > 0
+    dev_ws = torch.empty(ws_bytes + (4096 if chunk == 0 else 0), dtype=torch.uint8, device=DEV)
+    C_ooc = C0[0].to(DEV).clone()
+    a_ooc, n_ooc = fk.fk_lloyd_ooc(Xpin, C_ooc, 1, dev_ws=dev_ws, chunk_rows=chunk)
+    C_in = C0.to(DEV).clone()
+    a_in, n_in, _ = fk.fk_lloyd_iter(X.to(DEV), C_in, 1)
+    torch.cuda.synchronize()
+    assert torch.equal(a_ooc, a_in[0]) and torch.equal(n_ooc, n_in[0])
+    parity.check_centroids(C_ooc.cpu().numpy(), C_in[0].cpu().numpy(), 2e-6, "ooc vs in-core")
+    # and against the definition, over three more iterations
+    a3, n3 = fk.fk_lloyd_ooc(Xpin, C_ooc, 3, dev_ws=dev_ws, chunk_rows=chunk)
+    assert int(n3.sum()) == N
+    Xh = parity.widen(X[0])
+    u = oracle.update(Xh, a3.cpu().numpy(), C_ooc.cpu().numpy())
+    parity.check_centroids(C_ooc.cpu().numpy(), u["C"], parity.CENTROID_TOL[dtype])
+    assert (u["counts"] == n3.cpu().numpy()).all()
+
+
+def test_bad_arguments_are_errors_not_crashes():
+    X = torch.zeros((1, 128, 16), dtype=torch.float16, device=DEV)
+    C = torch.zeros((1, 4, 16), dtype=torch.float16, device=DEV)
+    small = torch.empty(256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(fk.FlashKMError) as e:
+        fk.fk_assign(X, C, ws=small)
+    assert e.value.status == 3
+    with pytest.raises(fk.FlashKMError) as e:
+        fk.fk_assign(torch.zeros((1, 8, 12), dtype=torch.float16, device=DEV),
+                     torch.zeros((1, 2, 12), dtype=torch.float16, device=DEV),
+                     ws=torch.empty(1 << 20, dtype=torch.uint8, device=DEV))
+    assert e.value.status == 2          # d not a multiple of 8
+    with pytest.raises(ValueError):
+        fk.fk_lloyd_ooc(torch.zeros((64, 16), dtype=torch.float16), C[0].float(), 1, dev_ws=small)
