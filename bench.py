@@ -1,0 +1,238 @@
+#!/usr/bin/env python3
+"""Benchmark of the Lloyd k-means hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c4|c5]
+
+A step is one full Lloyd iteration (fused assign, sort-inverse, segment reduction,
+merge/normalise) over a synthetic Gaussian mixture already resident in HBM.  The default
+workload is the headline one: N = 2^20, d = 128, K = 1024, fp16.  Prints ONE JSON line.
+
+The line carries, besides the throughput, the roofline of the dominant kernel (its
+algorithmic flops or bytes over its mean duration measured with HIP events inside the
+library, on the stream the kernels run on) and the fp64 CPU oracle timed on this machine's
+host cores as a reported baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+sys.path.insert(0, str(ROOT))
+
+PEAK_MFMA_F16_TFLOPS = 2500.0     # MI355X dense fp16 / bf16 MFMA
+PEAK_HBM_GBPS = 8000.0            # MI355X HBM3E
+PEAK_FP32_VALU_TFLOPS = 157.3
+
+
+def _traffic_from_profiles(kernel: str, workload: str):
+    """HBM bytes per launch measured offline with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+    read from profiles/<kernel>_<workload>_traffic.txt if that summary has been committed."""
+    f = ROOT / "profiles" / f"{kernel}_{workload}_traffic.txt"
+    if not f.exists():
+        return None
+    for line in f.read_text().splitlines():
+        if line.startswith("hbm_bytes_per_launch:"):
+            return float(line.split(":", 1)[1])
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run it with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2603_09229_amd import binding as fk
+    from paper_2603_09229_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    short = {"c1": wl.C1, "c2": wl.C2, "c3": wl.C3, "c4": wl.C4, "c5": wl.C5}
+    if args.workload not in short:
+        print(f"unknown workload {args.workload}", file=sys.stderr)
+        return 2
+    w = short[args.workload]
+    steps = args.steps if args.steps is not None else w.iters
+    if args.workload == "c5":
+        return bench_ooc(args, w, steps, torch, fk, wl, dev)
+
+    # ---------------------------------------------------------------- inputs (synthetic)
+    X, lab = wl.make_points(w, device=dev, return_labels=True)
+    idx = wl.init_rows(w, lab if w.zipf_s > 0 else None)
+    C0 = wl.gather_rows(X, idx).contiguous()
+    del lab
+    ws = fk.make_workspace(w.B, w.N, w.d, w.K, w.torch_dtype, dev)
+    C = C0.clone()
+    assign = torch.empty((w.B, w.N), dtype=torch.int32, device=dev)
+    counts = torch.empty((w.B, w.K), dtype=torch.int32, device=dev)
+    C_lp = torch.empty((w.B, w.K, w.d), dtype=w.torch_dtype, device=dev)
+
+    def run(iters):
+        fk.fk_lloyd_iter(X, C, iters, ws=ws, C_lp=C_lp, assign=assign, counts=counts)
+
+    # ---------------------------------------------------------------- throughput
+    if args.warmup > 0:
+        run(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / steps
+    assert int(counts.sum()) == w.B * w.N
+
+    # ---------------------------------------------------------------- per-stage (instrumented rerun)
+    C.copy_(C0)
+    if args.warmup > 0:
+        run(args.warmup)
+    torch.cuda.synchronize()
+    fk.fk_stage_timer_start()
+    run(steps)
+    stages = fk.fk_stage_timer_stop()
+    avg = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in stages.items()}   # ms per iteration
+
+    es = 4 if w.dtype == "fp32" else 2
+    flops = 2.0 * w.B * w.N * w.K * w.d
+    assign_tflops = flops / (avg["assign"] * 1e-3) / 1e12
+    assign_bytes = w.B * (w.N * w.d * es + w.K * w.d * es + 4 * w.K + 4 * w.N)
+    upd_bytes = w.B * (w.N * (w.d * es + 12) + w.K * w.d * (4 + es))
+    upd_ms = avg["sort"] + avg["reduce"] + avg["finalize"]
+    update_gbps = upd_bytes / (upd_ms * 1e-3) / 1e9
+
+    # dominant kernel: the assignment kernel wherever its contraction outweighs streaming X
+    # (K above the MFMA/HBM ridge of ~312 flop/byte); otherwise the update's row gather
+    if w.dtype != "fp32" and w.K >= 312:
+        roof = {"kernel": "assign_mfma_kernel", "bound": "mfma", "achieved": assign_tflops,
+                "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
+                "frac": assign_tflops / PEAK_MFMA_F16_TFLOPS,
+                "traffic": _traffic_from_profiles("assign_mfma_kernel", w.name),
+                "avg_launch_ms": avg["assign"]}
+    elif w.dtype == "fp32":
+        # 3 fp32 VALU flops (sub, mul, add) per (point, centroid, feature)
+        t = 1.5 * flops / (avg["assign"] * 1e-3) / 1e12
+        roof = {"kernel": "assign_f32_kernel", "bound": "alu", "achieved": t,
+                "peak": PEAK_FP32_VALU_TFLOPS, "unit": "TFLOP/s",
+                "frac": t / PEAK_FP32_VALU_TFLOPS, "traffic": None,
+                "avg_launch_ms": avg["assign"]}
+    else:
+        red_bytes = w.B * (w.N * (w.d * es + 4))
+        g = red_bytes / (avg["reduce"] * 1e-3) / 1e9
+        roof = {"kernel": "segment_reduce_kernel", "bound": "hbm", "achieved": g,
+                "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": g / PEAK_HBM_GBPS,
+                "traffic": _traffic_from_profiles("segment_reduce_kernel", w.name),
+                "avg_launch_ms": avg["reduce"]}
+
+    out = {
+        "metric": "lloyd_iterations_per_s",
+        "value": 1e3 / ms_per_step,
+        "unit": "iterations/s",
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"fp16": "f16", "bf16": "bf16", "fp32": "f32"}[w.dtype],
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "N": w.N, "d": w.d, "K": w.K,
+                   "storage": w.dtype, "accumulate": "f32"},
+        "assign_tflops": assign_tflops,
+        "assign_frac_of_mfma_peak": assign_tflops / PEAK_MFMA_F16_TFLOPS,
+        "assign_gbps": assign_bytes / (avg["assign"] * 1e-3) / 1e9,
+        "update_gbps": update_gbps,
+        "update_frac_of_hbm_peak": update_gbps / PEAK_HBM_GBPS,
+        "stage_ms": avg,
+        "roofline": roof,
+    }
+
+    # ---------------------------------------------------------------- CPU oracle baseline
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, X, C0, torch)
+    print(json.dumps(out))
+    return 0
+
+
+def cpu_baseline(w, X, C0, torch):
+    """The fp64 oracle as it stands, timed on this machine's host cores on a bounded sample."""
+    import numpy as np
+    import oracle
+    # sample: instance 0, the first n_s points against all K centroids, sized for ~10-20 s
+    budget_pairs = 6.0e11            # (point, centroid, feature) triples for the timed sample
+    n_s = int(min(w.N, max(1024, budget_pairs / (w.K * w.d) / 2)))
+    Xs = X[0, :n_s].to(torch.float32).cpu().numpy()
+    Cs = C0[0].cpu().numpy().astype(np.float64)
+    oracle.assign(Xs[:256], Cs)      # load the library, warm the threads
+    reps = 2
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        r = oracle.assign(Xs, Cs)
+        u = oracle.update(Xs, r["assign"], Cs)
+        Cs = u["C"]
+    dt = (time.perf_counter() - t0) / reps
+    full = dt * (w.N / n_s) * w.B    # one iteration over the whole workload, extrapolated
+    return {"value": 1.0 / full, "unit": "iterations/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"{reps} iterations (assign+update) on the first {n_s} of {w.N} points of "
+                      f"instance 0, all {w.K} centroids; {dt:.3f} s each, scaled by "
+                      f"{w.N / n_s * w.B:g} to the full workload"}
+
+
+def bench_ooc(args, w, steps, torch, fk, wl, dev):
+    """Out-of-core configuration: X in pinned host memory, streamed in chunks."""
+    cap = 32 << 30
+    N = int(os.environ.get("FK_OOC_ROWS", w.N))
+    w = w.scaled(N=N)
+    Xh = torch.empty((1, w.N, w.d), dtype=w.torch_dtype, pin_memory=True)
+    blk = 1 << 24
+    # same recipe as workloads.make_points, generated on the GPU block by block and copied
+    # down into the pinned buffer
+    torch.manual_seed(w.seed)
+    centres = torch.randn((w.K, w.d), device=dev) * w.center_std
+    for r0 in range(0, w.N, blk):
+        r1 = min(w.N, r0 + blk)
+        lab = torch.randint(0, w.K, (r1 - r0,), device=dev)
+        x = torch.randn((r1 - r0, w.d), device=dev).mul_(w.noise_std).add_(centres[lab])
+        Xh[0, r0:r1].copy_(x.to(w.torch_dtype))
+    del x, lab
+    idx = torch.randint(0, w.N, (w.K,), generator=torch.Generator().manual_seed(w.seed + 1000))
+    C = Xh[0][idx].to(torch.float32).to(dev).contiguous()
+    dev_ws = torch.empty(cap - (1 << 30), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    if args.warmup > 0:
+        fk.fk_lloyd_ooc(Xh[0], C, 1, dev_ws=dev_ws, keep_assign=False)
+    t0 = time.perf_counter()
+    a, counts = fk.fk_lloyd_ooc(Xh[0], C, steps, dev_ws=dev_ws, keep_assign=False)
+    elapsed = time.perf_counter() - t0
+    assert int(counts.sum()) == w.N
+    ms = elapsed * 1e3 / steps
+    flops = 2.0 * w.N * w.K * w.d
+    tf = flops / (ms * 1e-3) / 1e12
+    out = {"metric": "lloyd_iterations_per_s", "value": 1e3 / ms, "unit": "iterations/s",
+           "n_gpus": 1, "steps": steps, "warmup": min(args.warmup, 1), "ms_per_step": ms,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
+           "data": "synthetic",
+           "config": {"workload": w.name, "B": 1, "N": w.N, "d": w.d, "K": w.K,
+                      "storage": w.dtype, "device_cap_bytes": cap, "x": "pinned host"},
+           "end_to_end_tflops": tf,
+           "roofline": {"kernel": "assign_mfma_kernel", "bound": "mfma", "achieved": tf,
+                        "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
+                        "frac": tf / PEAK_MFMA_F16_TFLOPS, "traffic": None,
+                        "note": "whole iteration incl. PCIe streaming, not the kernel alone"}}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -143,6 +143,19 @@ fk_status fk_lloyd_ooc(const void* X_host, float* C_f32, int32_t* assign, int32_
 /* Device bytes fk_lloyd_ooc needs for `chunk_rows` rows per chunk; 0 if unsupported. */
 size_t fk_ooc_workspace_bytes(int64_t chunk_rows, int d, int K, fk_dtype t);
 
+/*
+ * Measurement aid (not a step of the method): while started, fk_lloyd_iter and fk_update
+ * record a HIP event on their stream after each stage of every iteration -- assignment
+ * kernel, sort-inverse, segment reduction, merge/normalise (with the centroid re-layout).
+ * fk_stage_timer_stop waits for the last event and returns, per stage in that order,
+ * the summed elapsed milliseconds and the number of intervals in stage_ms[4] /
+ * stage_launches[4] (host arrays); its return value is the number of events recorded, or -1
+ * on a HIP error.  One recorder per process, not thread safe; the events add a few
+ * microseconds per stage, so throughput is measured with the timer stopped.
+ */
+void fk_stage_timer_start(void);
+int fk_stage_timer_stop(double* stage_ms, int* stage_launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -20,7 +20,9 @@ _STATUS = {0: "FK_OK", 1: "FK_EINVAL", 2: "FK_EUNSUPPORTED", 3: "FK_EWORKSPACE",
 
 # every symbol include/flashkm.h declares
 EXPORTS = ("fk_last_error", "fk_workspace_bytes", "fk_assign", "fk_sort_inverse", "fk_update",
-           "fk_lloyd_iter", "fk_lloyd_ooc", "fk_ooc_workspace_bytes")
+           "fk_lloyd_iter", "fk_lloyd_ooc", "fk_ooc_workspace_bytes", "fk_stage_timer_start",
+           "fk_stage_timer_stop")
+STAGES = ("assign", "sort", "reduce", "finalize")
 
 
 class FlashKMError(RuntimeError):
@@ -58,6 +60,10 @@ def lib() -> ctypes.CDLL:
         L.fk_lloyd_iter.argtypes = [vp, vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, vp, sz, vp]
         L.fk_lloyd_ooc.restype = i32
         L.fk_lloyd_ooc.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, i32, i64, vp, sz, vp]
+        L.fk_stage_timer_start.restype = None
+        L.fk_stage_timer_start.argtypes = []
+        L.fk_stage_timer_stop.restype = i32
+        L.fk_stage_timer_stop.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
         _lib = L
     return _lib
 
@@ -187,3 +193,17 @@ def fk_lloyd_ooc(X_host, C_f32, iters: int, *, dev_ws, chunk_rows: int = 0, keep
                               _DTYPE[X_host.dtype], iters, chunk_rows, _ptr(dev_ws),
                               dev_ws.numel(), _stream(dev)))
     return a, counts
+
+
+def fk_stage_timer_start() -> None:
+    lib().fk_stage_timer_start()
+
+
+def fk_stage_timer_stop() -> dict:
+    """-> {stage: (total_ms, intervals)} for the stages recorded since the start call."""
+    ms = (ctypes.c_double * 4)()
+    n = (ctypes.c_int * 4)()
+    rc = lib().fk_stage_timer_stop(ms, n)
+    if rc < 0:
+        raise FlashKMError(4, "stage timer: HIP event error")
+    return {STAGES[i]: (float(ms[i]), int(n[i])) for i in range(4)}

@@ -4,6 +4,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <vector>
+
 #include "fk_common.h"
 
 namespace fk {
@@ -20,6 +22,30 @@ void set_error(const char* fmt, ...) {
 fk_status hip_fail(hipError_t e, const char* what) {
     set_error("HIP error %d (%s) in %s", (int)e, hipGetErrorString(e), what);
     return FK_EHIP;
+}
+
+// ---------------------------------------------------------------- stage timer
+// Optional HIP-event marks between the stages of an iteration (off by default; one process-
+// wide recorder, not thread safe: a measurement aid, not part of the compute path).
+enum { kStageAssign = 0, kStageSort = 1, kStageReduce = 2, kStageFinalize = 3, kStages = 4 };
+struct StageTimer {
+    bool on = false;
+    std::vector<hipEvent_t> pool;     // events owned by the recorder, reused across runs
+    size_t used = 0;
+    std::vector<int> stage;           // stage closed by mark i (-1 = opens an iteration)
+};
+static StageTimer g_timer;
+
+static void timer_mark(hipStream_t s, int stage) {
+    if (!g_timer.on) return;
+    if (g_timer.used == g_timer.pool.size()) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) { g_timer.on = false; return; }
+        g_timer.pool.push_back(e);
+    }
+    if (hipEventRecord(g_timer.pool[g_timer.used], s) != hipSuccess) { g_timer.on = false; return; }
+    g_timer.stage.push_back(stage);
+    ++g_timer.used;
 }
 
 static int ceil_log2(int v) {
@@ -165,8 +191,11 @@ static fk_status check_common(const char* fn, int B, int64_t N, int d, int K, fk
 static fk_status run_update(const Geometry& g, const Workspace& w, const void* X,
                             const int32_t* assign, const FinalizeArgs& fa, hipStream_t s) {
     FK_TRY(launch_sort_inverse(g, w, assign, w.sorted_idx, w.seg_off, w.item_off, s));
+    timer_mark(s, kStageSort);
     FK_TRY(launch_segment_reduce(g, w, X, w.sorted_idx, w.seg_off, w.item_off, s));
+    timer_mark(s, kStageReduce);
     FK_TRY(launch_finalize(g, w, w.seg_off, w.item_off, fa, s));
+    timer_mark(s, kStageFinalize);
     return FK_OK;
 }
 
@@ -177,6 +206,32 @@ using namespace fk;
 extern "C" {
 
 const char* fk_last_error(void) { return fk::g_err; }
+
+void fk_stage_timer_start(void) {
+    g_timer.used = 0;
+    g_timer.stage.clear();
+    g_timer.on = true;
+}
+
+int fk_stage_timer_stop(double* stage_ms, int* stage_launches) {
+    g_timer.on = false;
+    for (int i = 0; i < kStages; ++i) { stage_ms[i] = 0.0; stage_launches[i] = 0; }
+    if (g_timer.used == 0) return 0;
+    if (hipEventSynchronize(g_timer.pool[g_timer.used - 1]) != hipSuccess) return -1;
+    for (size_t i = 1; i < g_timer.used; ++i) {
+        int st = g_timer.stage[i];
+        // the gap between one iteration's last mark and the next iteration's opening mark
+        // is the centroid re-layout: booked under the merge/normalise stage
+        const bool relayout = st < 0 && g_timer.stage[i - 1] == kStageFinalize;
+        if (st < 0 && !relayout) continue;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g_timer.pool[i - 1], g_timer.pool[i]) != hipSuccess) return -1;
+        if (relayout) { stage_ms[kStageFinalize] += ms; continue; }
+        stage_ms[st] += ms;
+        stage_launches[st] += 1;
+    }
+    return (int)g_timer.used;
+}
 
 size_t fk_workspace_bytes(int B, int64_t N, int d, int K, fk_dtype t) {
     Geometry g;
@@ -247,6 +302,7 @@ fk_status fk_update(const void* X, const int32_t* assign, const float* C_prev_f3
     fa.sums = nullptr;
     fa.accumulate = false;
     fa.normalise = true;
+    timer_mark((hipStream_t)stream, -1);
     return run_update(g, w, X, assign, fa, (hipStream_t)stream);
 }
 
@@ -271,10 +327,12 @@ fk_status fk_lloyd_iter(const void* X, float* C_f32, void* C_lp, int32_t* assign
     // what the first assignment consumes: the master rounded to the storage type
     FK_TRY(launch_round_centroids(g, C_f32, t == FK_F32 ? nullptr : lp, w.c_frag, w.c_bias, s));
     for (int it = 0; it < iters; ++it) {
+        timer_mark(s, -1);
         if (t == FK_F32)
             FK_TRY(launch_assign(g, X, C_f32, nullptr, assign, nullptr, s));
         else
             FK_TRY(launch_assign(g, X, w.c_frag, w.c_bias, assign, nullptr, s));
+        timer_mark(s, kStageAssign);
         FinalizeArgs fa;
         fa.C_prev_f32 = C_f32;
         fa.C_out_f32 = C_f32;
