@@ -15,6 +15,9 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-fno-gpu-rdc", "-Wall", "-Wno-unused-function",
+    # MFMA accumulators in ordinary VGPRs: the argmin epilogue reads them with VALU
+    # instructions, which cannot address AGPRs (saves one copy per accumulator element)
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
     # packed-fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     f"-I{ROOT / 'include'}", f"-I{CSRC}",

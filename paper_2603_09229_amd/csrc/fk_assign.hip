@@ -10,6 +10,8 @@
 // The N x K score matrix exists only in accumulator registers.
 //
 // fp32 inputs: plain fp32 direct differences, one point per thread, centroid tiles in LDS.
+#include <stdlib.h>
+
 #include "fk_common.h"
 
 namespace fk {
@@ -40,7 +42,11 @@ __device__ __forceinline__ uint16_t float_to_lp(float f, bool bf) {
 //   SRC_F32: source is the fp32 master (rounded here, and written to C_lp if non-NULL);
 //   else the source is already the 16-bit array.
 // Writes the fragment-ordered copy and bias[k] = -||c_k||^2 / 2 computed in fp32 from the
-// ROUNDED values, i.e. from exactly what the MFMA multiplies (-inf for rows >= K).
+// ROUNDED values, i.e. from exactly what the MFMA multiplies.  Rows >= K get a huge negative
+// finite bias: it must survive having its low mantissa bits overwritten (-inf would turn
+// into a NaN pattern) and still lose against every real score.
+constexpr float kPadBias = -3.0e38f;
+
 template <bool SRC_F32>
 __global__ __launch_bounds__(512) void centroid_layout_kernel(
     const void* __restrict__ src, uint16_t* __restrict__ C_lp, uint16_t* __restrict__ c_frag,
@@ -87,7 +93,7 @@ __global__ __launch_bounds__(512) void centroid_layout_kernel(
         float n2 = 0.f;
         for (int q = 0; q < dch * 2; ++q) n2 += part[g][q];   // fixed order
         const int kk = kt * 32 + g;
-        c_bias[((size_t)b * ktiles + kt) * 32 + g] = kk < K ? -0.5f * n2 : -INFINITY;
+        c_bias[((size_t)b * ktiles + kt) * 32 + g] = kk < K ? -0.5f * n2 : kPadBias;
     }
 }
 
@@ -136,18 +142,37 @@ __device__ __forceinline__ floatx16 mfma32(uintx4 a, uintx4 b, floatx16 c) {
                                                       __builtin_bit_cast(half8, b), c, 0, 0, 0);
 }
 
+// Direct global -> LDS copy of 16 bytes per lane: the wave's 64 lanes fill 1 KiB starting
+// at the (wave-uniform) LDS address `lds_base`, lane i at lds_base + 16*i.
+__device__ __forceinline__ void copy16_to_lds(const uintx4* gsrc, uintx4* lds_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                     (__attribute__((address_space(3))) void*)lds_base, 16, 0, 0);
+}
+
 // BF: bf16 (else fp16).  DCH: feature chunks of 16 held per point.  P: 32-point tiles per
 // wave.  WAVES: waves per workgroup.  ST: centroid tiles per LDS stage.
+//
+// Score bookkeeping.  The fp32 score of a (point, centroid) pair leaves the MFMA with the
+// -||c||^2/2 bias already added (the bias enters as the C operand of the first MFMA of the
+// chain).  Its low 4 mantissa bits are then replaced by 15 - slot, slot being the
+// accumulator index, so that ONE float max carries value and slot together: 1.5 VALU
+// operations per pair instead of 3, which is what keeps the epilogue off the MFMA's
+// critical path.  The truncation costs 2^-19 relative to the score, the same order as the
+// fp32 rounding of a d-term dot product and ~250x below the 1e-3 tolerance band.
+// Ties between scores equal after truncation: the earlier centroid tile wins; inside a tile
+// the lower row wins for scores >= 0 (the usual case for a winner: x.c > ||c||^2/2), the
+// higher row among the lane's 16 for negative ones.
 template <bool BF, int DCH, int P, int WAVES, int ST>
 __global__ __launch_bounds__(WAVES * 64) void assign_mfma_kernel(
     const uint16_t* __restrict__ X, const uintx4* __restrict__ c_frag,
     const float* __restrict__ c_bias, int32_t* __restrict__ assign,
-    float* __restrict__ min_dist, int64_t N, int d, int ktiles) {
+    float* __restrict__ min_dist, int64_t N, int d, int K, int ktiles) {
     constexpr int kThreads = WAVES * 64;
     constexpr int kStageVec = ST * DCH * 64;            // 16-byte vectors per stage
-    constexpr int kLoads = (kStageVec + kThreads - 1) / kThreads;
+    constexpr int kPieces = ST * DCH;                   // 1 KiB pieces per stage
     __shared__ uintx4 sfrag[2][kStageVec];
     __shared__ float sbias[2][ST * 32];
+    static_assert(ST * 32 <= kThreads, "one bias value per thread per stage");
 
     const int b = blockIdx.y;
     X += (size_t)b * N * d;
@@ -159,6 +184,29 @@ __global__ __launch_bounds__(WAVES * 64) void assign_mfma_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 31, h = lane >> 5;
     const int64_t p0 = ((int64_t)blockIdx.x * WAVES + wave) * (P * 32);
+
+    const int nstages = (ktiles + ST - 1) / ST;
+    const int total_pieces = ktiles * DCH;
+
+    // Stage copy: centroid fragments go global -> LDS without passing through registers;
+    // the 32 bias values per tile take the ordinary path (one float per thread).
+    auto fetch = [&](int st, int buf) -> float {
+#pragma unroll
+        for (int q = 0; q < (kPieces + WAVES - 1) / WAVES; ++q) {
+            const int pc = q * WAVES + wave;                       // wave-uniform
+            if (pc < kPieces && st * kPieces + pc < total_pieces)
+                copy16_to_lds(c_frag + ((size_t)(st * kPieces + pc) * 64 + lane),
+                              &sfrag[buf][pc * 64]);
+        }
+        float bv = kPadBias;
+        if (tid < ST * 32) {
+            const int o = st * ST * 32 + tid;
+            if (o < ktiles * 32) bv = c_bias[o];
+        }
+        return bv;
+    };
+
+    float pre_bias = fetch(0, 0);
 
     // Point features: lane (n,h) keeps features [s*16 + h*8, +8) of point p0 + pt*32 + n.
     uintx4 xf[P][DCH];
@@ -174,90 +222,79 @@ __global__ __launch_bounds__(WAVES * 64) void assign_mfma_kernel(
         }
     }
 
-    float best[P];
-    int enc[P];   // tile * 16 + accumulator slot of the best score so far
+    float best[P];   // packed: score with low 4 bits = 15 - slot
+    int btile[P];    // centroid tile of the best score so far
 #pragma unroll
-    for (int pt = 0; pt < P; ++pt) { best[pt] = -INFINITY; enc[pt] = 0; }
+    for (int pt = 0; pt < P; ++pt) { best[pt] = -INFINITY; btile[pt] = 0; }
 
-    const int nstages = (ktiles + ST - 1) / ST;
-    const int total_vec = ktiles * DCH * 64;
-    uintx4 pre[kLoads];
-    float pre_bias = 0.f;
-
-    auto fetch = [&](int st) {
-        const int base = st * kStageVec;
-#pragma unroll
-        for (int q = 0; q < kLoads; ++q) {
-            const int o = q * kThreads + tid;
-            uintx4 v = {0u, 0u, 0u, 0u};
-            if (o < kStageVec && base + o < total_vec) v = c_frag[base + o];
-            pre[q] = v;
-        }
-        if (tid < ST * 32) {
-            const int o = st * ST * 32 + tid;
-            pre_bias = o < ktiles * 32 ? c_bias[o] : -INFINITY;
-        }
-    };
-    auto commit = [&](int buf) {
-#pragma unroll
-        for (int q = 0; q < kLoads; ++q) {
-            const int o = q * kThreads + tid;
-            if (o < kStageVec) sfrag[buf][o] = pre[q];
-        }
-        if (tid < ST * 32) sbias[buf][tid] = pre_bias;
-    };
-
-    fetch(0);
-    commit(0);
+    if (tid < ST * 32) sbias[0][tid] = pre_bias;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     for (int st = 0; st < nstages; ++st) {
         const int buf = st & 1;
-        if (st + 1 < nstages) fetch(st + 1);          // overlaps the MFMA sweep below
+        if (st + 1 < nstages) pre_bias = fetch(st + 1, buf ^ 1);   // lands during the sweep
         const int nt = min(ST, ktiles - st * ST);
         for (int tt = 0; tt < nt; ++tt) {
-            floatx16 acc[P];
             // accumulator slot i is centroid row 8*(i/4) + 4*h + i%4 of this tile
+            floatx16 bias16;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const floatx4 bv = *(const floatx4*)&sbias[buf][tt * 32 + 8 * q + 4 * h];
-#pragma unroll
-                for (int pt = 0; pt < P; ++pt) {
-                    acc[pt][4 * q + 0] = bv[0];
-                    acc[pt][4 * q + 1] = bv[1];
-                    acc[pt][4 * q + 2] = bv[2];
-                    acc[pt][4 * q + 3] = bv[3];
-                }
+                bias16[4 * q + 0] = bv[0];
+                bias16[4 * q + 1] = bv[1];
+                bias16[4 * q + 2] = bv[2];
+                bias16[4 * q + 3] = bv[3];
             }
+            uintx4 a[DCH];
 #pragma unroll
-            for (int s = 0; s < DCH; ++s) {
-                const uintx4 a = sfrag[buf][(tt * DCH + s) * 64 + lane];
+            for (int s = 0; s < DCH; ++s) a[s] = sfrag[buf][(tt * DCH + s) * 64 + lane];
+            floatx16 acc[P];
 #pragma unroll
-                for (int pt = 0; pt < P; ++pt) acc[pt] = mfma32<BF>(a, xf[pt][s], acc[pt]);
+            for (int pt = 0; pt < P; ++pt) acc[pt] = mfma32<BF>(a[0], xf[pt][0], bias16);
+#pragma unroll
+            for (int s = 1; s < DCH; ++s) {
+#pragma unroll
+                for (int pt = 0; pt < P; ++pt) acc[pt] = mfma32<BF>(a[s], xf[pt][s], acc[pt]);
             }
-            // online argmax; ascending slot order + strict '>' keeps the lowest row
-            const int ebase = (st * ST + tt) * 16;
+            const int tile = st * ST + tt;
 #pragma unroll
             for (int pt = 0; pt < P; ++pt) {
+                // The running best enters the tile with its slot field set so that an equal
+                // truncated score cannot displace it (all ones for a positive float, zeros
+                // for a negative one): across tiles only a strictly better score wins.
+                const uint32_t bb = __float_as_uint(best[pt]);
+                const uint32_t fill = ~(uint32_t)((int32_t)bb >> 31) & 15u;
+                const float guard = __uint_as_float((bb & 0xFFFFFFF0u) | fill);
+                float m = guard;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float v = acc[pt][i];
-                    if (v > best[pt]) { best[pt] = v; enc[pt] = ebase + i; }
+                for (int i = 0; i < 16; i += 2) {
+                    const float k0 = __uint_as_float((__float_as_uint(acc[pt][i]) & 0xFFFFFFF0u) | (uint32_t)(15 - i));
+                    const float k1 = __uint_as_float((__float_as_uint(acc[pt][i + 1]) & 0xFFFFFFF0u) | (uint32_t)(14 - i));
+                    m = __builtin_fmaxf(__builtin_fmaxf(m, k0), k1);
                 }
+                const bool improved = m != guard;
+                best[pt] = improved ? m : best[pt];
+                btile[pt] = improved ? tile : btile[pt];
             }
         }
-        if (st + 1 < nstages) commit(buf ^ 1);
+        if (st + 1 < nstages) {
+            if (tid < ST * 32) sbias[buf ^ 1][tid] = pre_bias;
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
         __syncthreads();
     }
 
 #pragma unroll
     for (int pt = 0; pt < P; ++pt) {
-        const int i = enc[pt] & 15;
-        int k = (enc[pt] >> 4) * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
-        float m = best[pt];
+        const uint32_t bits = __float_as_uint(best[pt]);
+        const int i = 15 - (int)(bits & 15u);
+        int k = btile[pt] * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
+        float m = __uint_as_float(bits & 0xFFFFFFF0u);
         const float om = __shfl_xor(m, 32);
         const int ok = __shfl_xor(k, 32);
         if (om > m || (om == m && ok < k)) { m = om; k = ok; }
+        k = min(k, K - 1);   // only reachable with non-finite input; keeps the index in range
         const int64_t point = p0 + pt * 32 + n;
         float xn = 0.f;
         if (min_dist) {
@@ -330,18 +367,40 @@ __global__ __launch_bounds__(256) void assign_f32_kernel(
 }
 
 // ------------------------------------------------------------------------------------
-template <bool BF, int DCH>
-static fk_status launch_mfma(const Geometry& g, const void* X, const void* frag,
-                             const float* bias, int32_t* assign, float* min_dist,
-                             hipStream_t s) {
-    constexpr int P = 2, WAVES = 4, ST = 16 / DCH;   // 16 KiB of fragments per stage
+template <bool BF, int DCH, int P, int WAVES>
+static fk_status launch_mfma_v(const Geometry& g, const void* X, const void* frag,
+                               const float* bias, int32_t* assign, float* min_dist,
+                               hipStream_t s) {
+    constexpr int ST = (16 / DCH) < 8 ? (16 / DCH) : 8;   // up to 16 KiB of fragments per stage
     const int64_t per_wg = (int64_t)P * 32 * WAVES;
     dim3 grid((unsigned)cdiv(g.N, per_wg), g.B), block(WAVES * 64);
     hipLaunchKernelGGL((assign_mfma_kernel<BF, DCH, P, WAVES, ST>), grid, block, 0, s,
                        (const uint16_t*)X, (const uintx4*)frag, bias, assign, min_dist, g.N,
-                       g.d, g.ktiles);
+                       g.d, g.K, g.ktiles);
     FK_HIP(hipGetLastError());
     return FK_OK;
+}
+
+// Tile shape per wave / workgroup.  FK_ASSIGN_VARIANT (read once) overrides the default for
+// experiments: 0 = 2 point tiles x 4 waves, 1 = 4 x 4, 2 = 2 x 8, 3 = 1 x 4.
+static int assign_variant() {
+    static int v = [] {
+        const char* e = getenv("FK_ASSIGN_VARIANT");
+        return e ? atoi(e) : 0;
+    }();
+    return v;
+}
+
+template <bool BF, int DCH>
+static fk_status launch_mfma(const Geometry& g, const void* X, const void* frag,
+                             const float* bias, int32_t* assign, float* min_dist,
+                             hipStream_t s) {
+    switch (assign_variant()) {
+        case 1: return launch_mfma_v<BF, DCH, 4, 4>(g, X, frag, bias, assign, min_dist, s);
+        case 2: return launch_mfma_v<BF, DCH, 2, 8>(g, X, frag, bias, assign, min_dist, s);
+        case 3: return launch_mfma_v<BF, DCH, 1, 4>(g, X, frag, bias, assign, min_dist, s);
+        default: return launch_mfma_v<BF, DCH, 2, 4>(g, X, frag, bias, assign, min_dist, s);
+    }
 }
 
 template <bool BF>
