@@ -75,14 +75,13 @@ bool make_geometry(int B, int64_t N, int d, int K, fk_dtype t, Geometry* g) {
         g->pass_bits[1] = g->sort_bits - g->pass_bits[0];
         nbmax = 1 << g->pass_bits[1];
     }
-    int64_t T = 16 * (int64_t)nbmax;
-    if (T < cdiv(N, 512)) T = cdiv(N, 512);
-    if (T < 1024) T = 1024;
-    T = cdiv(T, 1024) * 1024;
+    // sort workgroups own whole sub-tiles of 4096 keys; at most 4096 workgroups per instance
+    (void)nbmax;
+    int64_t T = 4096 * cdiv(N, (int64_t)4096 * 4096);
     g->sort_tile = (int)T;
     g->sort_blocks = (int)cdiv(N, T);
-    int64_t R = cdiv(N, 8192);
-    if (R < 64) R = 64;
+    int64_t R = cdiv(N, 4096);
+    if (R < 256) R = 256;
     g->rows_per_item = (int)R;
     g->max_items = N / R + K;
     return true;
@@ -298,6 +297,8 @@ fk_status fk_update(const void* X, const int32_t* assign, const float* C_prev_f3
     fa.C_prev_f32 = C_prev_f32;
     fa.C_out_f32 = C_out_f32;
     fa.C_out_lp = C_out_lp;
+    fa.c_frag = nullptr;
+    fa.c_bias = nullptr;
     fa.counts = counts;
     fa.sums = nullptr;
     fa.accumulate = false;
@@ -337,13 +338,13 @@ fk_status fk_lloyd_iter(const void* X, float* C_f32, void* C_lp, int32_t* assign
         fa.C_prev_f32 = C_f32;
         fa.C_out_f32 = C_f32;
         fa.C_out_lp = (t == FK_F32) ? (it + 1 == iters ? C_lp : nullptr) : lp;
+        fa.c_frag = w.c_frag;      // re-laid out for the next assignment by the same kernel
+        fa.c_bias = w.c_bias;
         fa.counts = counts;
         fa.sums = nullptr;
         fa.accumulate = false;
         fa.normalise = true;
         FK_TRY(run_update(g, w, X, assign, fa, s));
-        if (t != FK_F32 && it + 1 < iters)
-            FK_TRY(launch_prepare_centroids(g, lp, w.c_frag, w.c_bias, s));
     }
     return FK_OK;
 }

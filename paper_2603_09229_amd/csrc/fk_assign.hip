@@ -80,7 +80,7 @@ __global__ __launch_bounds__(512) void centroid_layout_kernel(
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float f = lp_to_float(v[e], bf);
-                ss += f * f;
+                ss = __fadd_rn(ss, __fmul_rn(f, f));   // no FMA: the update kernel repeats this sum bit for bit
             }
         }
         uint16_t* q = c_frag + ((((size_t)b * ktiles + kt) * dch + s) * 64 + l) * 8;
@@ -382,11 +382,11 @@ static fk_status launch_mfma_v(const Geometry& g, const void* X, const void* fra
 }
 
 // Tile shape per wave / workgroup.  FK_ASSIGN_VARIANT (read once) overrides the default for
-// experiments: 0 = 2 point tiles x 4 waves, 1 = 4 x 4, 2 = 2 x 8, 3 = 1 x 4.
+// experiments: 0 = 2 point tiles x 4 waves, 1 = 4 x 4, 2 = 2 x 8 (default), 3 = 1 x 4.
 static int assign_variant() {
     static int v = [] {
         const char* e = getenv("FK_ASSIGN_VARIANT");
-        return e ? atoi(e) : 0;
+        return e ? atoi(e) : 2;
     }();
     return v;
 }
@@ -397,9 +397,9 @@ static fk_status launch_mfma(const Geometry& g, const void* X, const void* frag,
                              hipStream_t s) {
     switch (assign_variant()) {
         case 1: return launch_mfma_v<BF, DCH, 4, 4>(g, X, frag, bias, assign, min_dist, s);
-        case 2: return launch_mfma_v<BF, DCH, 2, 8>(g, X, frag, bias, assign, min_dist, s);
+        case 0: return launch_mfma_v<BF, DCH, 2, 4>(g, X, frag, bias, assign, min_dist, s);
         case 3: return launch_mfma_v<BF, DCH, 1, 4>(g, X, frag, bias, assign, min_dist, s);
-        default: return launch_mfma_v<BF, DCH, 2, 4>(g, X, frag, bias, assign, min_dist, s);
+        default: return launch_mfma_v<BF, DCH, 2, 8>(g, X, frag, bias, assign, min_dist, s);
     }
 }
 

@@ -162,6 +162,8 @@ fk_status fk_lloyd_ooc(const void* X_host, float* C_f32, int32_t* assign, int32_
             fa.C_prev_f32 = C_f32;
             fa.C_out_f32 = C_f32;
             fa.C_out_lp = nullptr;
+            fa.c_frag = nullptr;
+            fa.c_bias = nullptr;
             fa.counts = counts;
             fa.sums = wfull.sums;
             fa.accumulate = c > 0;

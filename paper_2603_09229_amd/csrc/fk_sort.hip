@@ -67,77 +67,110 @@ __device__ int block_exclusive_scan(int* v, int n, int* scratch) {
 }  // namespace
 
 // ------------------------------------------------------------------------------------
-// Per-workgroup digit histogram.  Workgroup `blk` of instance b owns keys
-// [blk*T, min(N,(blk+1)*T)); writes H[b][blk][0..NB).
-__global__ __launch_bounds__(1024) void sort_hist_kernel(
-    const int32_t* __restrict__ keys, int32_t* __restrict__ H, int64_t N, int T, int NB,
-    int shift, int mask, int kmax, int nbits) {
+// Tiling shared by the histogram and scatter kernels: a workgroup of 256 threads owns
+// `rounds` consecutive sub-tiles of 4096 keys; inside a sub-tile wave w owns keys
+// [w*1024, (w+1)*1024) as 16 batches of 64, batch j at offset j*64 + lane.  All 16 loads of
+// a round are issued before any is used.
+constexpr int kSortThreads = 256;
+constexpr int kSortWaves = 4;
+constexpr int kBatches = 16;                 // batches of 64 keys per wave per round
+constexpr int kSubTile = kSortWaves * kBatches * 64;   // 4096
+
+// Keys come back clamped to [0, kmax]; -1 marks a lane past the end of the array.
+__device__ __forceinline__ void load_round(const int32_t* __restrict__ keys, int64_t base,
+                                           int64_t N, int lane, int kmax, int (&k)[kBatches]) {
+#pragma unroll
+    for (int j = 0; j < kBatches; ++j) {
+        const int64_t i = base + j * 64 + lane;
+        k[j] = i < N ? keys[i] : -1;
+    }
+#pragma unroll
+    for (int j = 0; j < kBatches; ++j) {
+        const int64_t i = base + j * 64 + lane;
+        k[j] = i < N ? clamp_key(k[j], kmax) : -1;
+    }
+}
+
+// Per-workgroup digit histogram, written transposed: H[b][bin][blk].
+__global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(
+    const int32_t* __restrict__ keys, int32_t* __restrict__ H, int64_t N, int rounds, int NB,
+    int shift, int mask, int kmax) {
     extern __shared__ int lds[];
     int* hist = lds;
     const int b = blockIdx.y, blk = blockIdx.x, nb = gridDim.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     keys += (size_t)b * N;
-    for (int i = threadIdx.x; i < NB; i += blockDim.x) hist[i] = 0;
+    for (int i = tid; i < NB; i += kSortThreads) hist[i] = 0;
     __syncthreads();
-    const int64_t lo = (int64_t)blk * T, hi = min(N, lo + T);
-    for (int64_t i0 = lo; i0 < hi; i0 += blockDim.x) {
-        const int64_t i = i0 + threadIdx.x;
-        const bool valid = i < hi;
-        const int digit = valid ? (clamp_key(keys[i], kmax) >> shift) & mask : 0;
-        const uint64_t peers = match_digit(digit, nbits, __ballot(valid));
-        // one LDS add per distinct digit per wave keeps hot bins from serialising
-        if (valid && (peers & lanemask_lt()) == 0) atomicAdd(&hist[digit], __popcll(peers));
-    }
-    __syncthreads();
-    int32_t* out = H + ((size_t)b * nb + blk) * NB;
-    for (int i = threadIdx.x; i < NB; i += blockDim.x) out[i] = hist[i];
-}
-
-// Exclusive scan of H along the workgroup axis, per bin, in place; tot[b][bin] = column sum.
-// A workgroup of 256 threads covers BG bins x (256/BG) contiguous ranges of workgroups.
-__global__ __launch_bounds__(256) void sort_binscan_kernel(int32_t* __restrict__ H,
-                                                           int32_t* __restrict__ tot, int nb,
-                                                           int NB, int bg_log2) {
-    __shared__ int ssum[256];
-    const int b = blockIdx.y;
-    const int BG = 1 << bg_log2, SEG = 256 >> bg_log2;
-    const int binl = threadIdx.x & (BG - 1), seg = threadIdx.x >> bg_log2;
-    const int bin = blockIdx.x * BG + binl;
-    const int per = (nb + SEG - 1) / SEG;
-    const int lo = min(nb, seg * per), hi = min(nb, lo + per);
-    int32_t* col = H + (size_t)b * nb * NB + bin;
-    int sum = 0;
-    if (bin < NB)
-        for (int r = lo; r < hi; ++r) sum += col[(size_t)r * NB];
-    ssum[threadIdx.x] = sum;
-    __syncthreads();
-    int run = 0;
-    for (int s2 = 0; s2 < seg; ++s2) run += ssum[(s2 << bg_log2) + binl];
-    if (bin < NB) {
-        if (seg == SEG - 1) tot[(size_t)b * NB + bin] = run + sum;
-        for (int r = lo; r < hi; ++r) {
-            const int t = col[(size_t)r * NB];
-            col[(size_t)r * NB] = run;
-            run += t;
+    int mine = 0;                              // small NB: lane b counts bin b for its wave
+    for (int r = 0; r < rounds; ++r) {
+        const int64_t base = ((int64_t)blk * rounds + r) * kSubTile + wave * (kBatches * 64);
+        if (base >= N) break;
+        int k[kBatches];
+        load_round(keys, base, N, lane, kmax, k);
+        if (NB <= 32) {
+            // hot bins would serialise LDS atomics: count with ballots instead
+#pragma unroll
+            for (int j = 0; j < kBatches; ++j) {
+                const int digit = k[j] < 0 ? -1 : (k[j] >> shift) & mask;
+                for (int bin = 0; bin < NB; ++bin) {
+                    const int c = __popcll(__ballot(digit == bin));
+                    if (lane == bin) mine += c;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < kBatches; ++j)
+                if (k[j] >= 0) atomicAdd(&hist[(k[j] >> shift) & mask], 1);
         }
     }
+    if (NB <= 32 && lane < NB && mine) atomicAdd(&hist[lane], mine);
+    __syncthreads();
+    int32_t* out = H + (size_t)b * NB * nb + blk;
+    for (int i = tid; i < NB; i += kSortThreads) out[(size_t)i * nb] = hist[i];
 }
 
-// Stable scatter.  Each wave owns a contiguous sub-range of the workgroup's keys and walks
-// it in order, so equal keys keep their input order.
+// Exclusive scan of H[b][bin][0..nb) in place, one wave per bin; tot[b][bin] = row sum.
+__global__ __launch_bounds__(256) void sort_binscan_kernel(int32_t* __restrict__ H,
+                                                           int32_t* __restrict__ tot, int nb,
+                                                           int NB) {
+    const int b = blockIdx.y, lane = threadIdx.x & 63;
+    const int bin = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (bin >= NB) return;
+    int32_t* row = H + ((size_t)b * NB + bin) * nb;
+    const int per = (nb + 63) >> 6;
+    const int lo = min(nb, lane * per), hi = min(nb, lo + per);
+    int sum = 0;
+    for (int i = lo; i < hi; ++i) sum += row[i];
+    int inc = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+    }
+    if (lane == 63) tot[(size_t)b * NB + bin] = inc;
+    int run = inc - sum;
+    for (int i = lo; i < hi; ++i) {
+        const int t = row[i];
+        row[i] = run;
+        run += t;
+    }
+}
+
+// Stable scatter.  Waves walk their keys in input order, so equal keys keep their order.
 //   vals_in == NULL: values are the key positions (first pass).
 //   keys_out may be NULL.  seg_off / item_off are written by workgroup 0 when non-NULL
 //   (single-pass sort: bins are cluster ids, so the bin offsets are the segment table).
-__global__ __launch_bounds__(1024) void sort_scatter_kernel(
+__global__ __launch_bounds__(kSortThreads) void sort_scatter_kernel(
     const int32_t* __restrict__ keys, const int32_t* __restrict__ vals_in,
     const int32_t* __restrict__ H, const int32_t* __restrict__ tot,
     int32_t* __restrict__ vals_out, int32_t* __restrict__ keys_out,
-    int32_t* __restrict__ seg_off, int32_t* __restrict__ item_off, int64_t N, int T, int NB,
-    int shift, int mask, int kmax, int nbits, int R) {
+    int32_t* __restrict__ seg_off, int32_t* __restrict__ item_off, int64_t N, int rounds,
+    int NB, int shift, int mask, int kmax, int nbits, int R) {
     extern __shared__ int lds[];
-    const int waves = blockDim.x >> 6;
     int* off = lds;                    // [NB]
     int* scratch = off + NB;           // [40]
-    int* wcnt = scratch + 40;          // [waves][NB]
+    int* wcnt = scratch + 40;          // [kSortWaves][NB]
     const int b = blockIdx.y, blk = blockIdx.x, nb = gridDim.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     keys += (size_t)b * N;
@@ -145,69 +178,100 @@ __global__ __launch_bounds__(1024) void sort_scatter_kernel(
     vals_out += (size_t)b * N;
     if (keys_out) keys_out += (size_t)b * N;
     tot += (size_t)b * NB;
-    H += ((size_t)b * nb + blk) * NB;
+    H += (size_t)b * NB * nb + blk;
+
+    // first round's keys are requested before the offset scans below need them
+    int k[kBatches];
+    const int64_t base0 = (int64_t)blk * rounds * kSubTile + wave * (kBatches * 64);
+    load_round(keys, base0, N, lane, kmax, k);
 
     if (item_off && blk == 0) {
         // exclusive scan of ceil(n_k / R): where each cluster's items start
-        for (int i = tid; i < NB; i += blockDim.x) off[i] = (tot[i] + R - 1) / R;
+        for (int i = tid; i < NB; i += kSortThreads) off[i] = (tot[i] + R - 1) / R;
         __syncthreads();
         const int total = block_exclusive_scan(off, NB, scratch);
         int32_t* io = item_off + (size_t)b * (NB + 1);
-        for (int i = tid; i < NB; i += blockDim.x) io[i] = off[i];
+        for (int i = tid; i < NB; i += kSortThreads) io[i] = off[i];
         if (tid == 0) io[NB] = total;
         __syncthreads();
     }
-    for (int i = tid; i < NB; i += blockDim.x) off[i] = tot[i];
-    for (int i = tid; i < waves * NB; i += blockDim.x) wcnt[i] = 0;
+    for (int i = tid; i < NB; i += kSortThreads) off[i] = tot[i];
+    for (int i = tid; i < kSortWaves * NB; i += kSortThreads) wcnt[i] = 0;
     __syncthreads();
     const int total = block_exclusive_scan(off, NB, scratch);
     if (seg_off && blk == 0) {
         int32_t* so = seg_off + (size_t)b * (NB + 1);
-        for (int i = tid; i < NB; i += blockDim.x) so[i] = off[i];
+        for (int i = tid; i < NB; i += kSortThreads) so[i] = off[i];
         if (tid == 0) so[NB] = total;
     }
 
-    const int tw = T / waves;          // keys per wave, a multiple of 64
-    const int64_t lo = (int64_t)blk * T + (int64_t)wave * tw;
-    const int64_t hi = min(N, lo + tw);
     int* mine = wcnt + wave * NB;
-    // pass 1: count this wave's digits
-    for (int64_t i0 = lo; i0 < hi; i0 += 64) {
-        const int64_t i = i0 + lane;
-        const bool valid = i < hi;
-        const int digit = valid ? (clamp_key(keys[i], kmax) >> shift) & mask : 0;
-        const uint64_t peers = match_digit(digit, nbits, __ballot(valid));
-        if (valid && (peers & lanemask_lt()) == 0) mine[digit] += __popcll(peers);
-        __builtin_amdgcn_wave_barrier();
+    const uint64_t lt = lanemask_lt();
+    // info[j] = rank among equal digits of the batch | (size of that group << 8)
+    int info[kBatches];
+    auto rank_round = [&](bool count) {
+#pragma unroll
+        for (int j = 0; j < kBatches; ++j) {
+            const bool valid = k[j] >= 0;
+            const int digit = valid ? (k[j] >> shift) & mask : 0;
+            const uint64_t peers = match_digit(digit, nbits, __ballot(valid));
+            const int rank = __popcll(peers & lt), cnt = __popcll(peers);
+            info[j] = rank | (cnt << 8);
+            if (count && valid && rank == 0) mine[digit] += cnt;
+            __builtin_amdgcn_wave_barrier();
+        }
+    };
+    // pass 1: per-wave digit counts
+    rank_round(true);
+    for (int r = 1; r < rounds; ++r) {
+        const int64_t base = base0 + (int64_t)r * kSubTile;
+        if (base >= N) break;
+        load_round(keys, base, N, lane, kmax, k);
+        rank_round(true);
     }
     __syncthreads();
-    // turn counts into start positions: global bin offset + earlier workgroups + earlier waves
-    for (int i = tid; i < NB; i += blockDim.x) {
-        int run = off[i] + H[i];
-        for (int w = 0; w < waves; ++w) {
+    // counts -> start positions: global bin offset + earlier workgroups + earlier waves
+    for (int i = tid; i < NB; i += kSortThreads) {
+        int run = off[i] + H[(size_t)i * nb];
+        for (int w = 0; w < kSortWaves; ++w) {
             const int t = wcnt[w * NB + i];
             wcnt[w * NB + i] = run;
             run += t;
         }
     }
     __syncthreads();
-    // pass 2: rank inside each 64-key batch, write, advance the wave's cursors
-    for (int64_t i0 = lo; i0 < hi; i0 += 64) {
-        const int64_t i = i0 + lane;
-        const bool valid = i < hi;
-        const int key = valid ? clamp_key(keys[i], kmax) : 0;
-        const int digit = (key >> shift) & mask;
-        const uint64_t peers = match_digit(digit, nbits, __ballot(valid));
-        const int rank = __popcll(peers & lanemask_lt());
-        int pos = 0;
-        if (valid) pos = mine[digit] + rank;
-        __builtin_amdgcn_wave_barrier();
-        if (valid) {
-            vals_out[pos] = vals_in ? vals_in[i] : (int32_t)i;
-            if (keys_out) keys_out[pos] = key;
-            if (rank == 0) mine[digit] += __popcll(peers);
+    // pass 2: write, advancing the wave's cursors batch by batch
+    for (int r = 0; r < rounds; ++r) {
+        const int64_t base = base0 + (int64_t)r * kSubTile;
+        if (base >= N) break;
+        if (rounds > 1) {                       // single round: keys and ranks are still here
+            load_round(keys, base, N, lane, kmax, k);
+            rank_round(false);
         }
-        __builtin_amdgcn_wave_barrier();
+        int v[kBatches];
+        if (vals_in) {
+#pragma unroll
+            for (int j = 0; j < kBatches; ++j) {
+                const int64_t i = base + j * 64 + lane;
+                v[j] = i < N ? vals_in[i] : 0;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kBatches; ++j) {
+            const bool valid = k[j] >= 0;
+            const int key = valid ? k[j] : 0;
+            const int digit = (key >> shift) & mask;
+            const int rank = info[j] & 255, cnt = info[j] >> 8;
+            int pos = 0;
+            if (valid) pos = mine[digit] + rank;
+            __builtin_amdgcn_wave_barrier();
+            if (valid) {
+                vals_out[pos] = vals_in ? v[j] : (int32_t)(base + j * 64 + lane);
+                if (keys_out) keys_out[pos] = key;
+                if (rank == 0) mine[digit] += cnt;
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
     }
 }
 
@@ -262,22 +326,19 @@ static fk_status sort_pass(const Geometry& g, const Workspace& w, const int32_t*
                            int32_t* seg_off, int32_t* item_off, int NB, int shift, int mask,
                            hipStream_t s) {
     const int nbits = ceil_log2(NB) < 1 ? 1 : ceil_log2(NB);
-    const int waves = NB <= 512 ? 16 : (NB <= 1024 ? 8 : 4);
-    const int threads = waves * 64;
+    const int rounds = g.sort_tile / kSubTile;
     int32_t* H = w.block_hist;
     int32_t* tot = w.digit_off;
     dim3 grid(g.sort_blocks, g.B);
-    hipLaunchKernelGGL(sort_hist_kernel, grid, dim3(1024), NB * sizeof(int), s, keys, H, g.N,
-                       g.sort_tile, NB, shift, mask, g.K - 1, nbits);
+    hipLaunchKernelGGL(sort_hist_kernel, grid, dim3(kSortThreads), NB * sizeof(int), s, keys, H,
+                       g.N, rounds, NB, shift, mask, g.K - 1);
     FK_HIP(hipGetLastError());
-    int bg_log2 = ceil_log2(NB);
-    if (bg_log2 > 6) bg_log2 = 6;
-    hipLaunchKernelGGL(sort_binscan_kernel, dim3((unsigned)cdiv(NB, 1 << bg_log2), g.B),
-                       dim3(256), 0, s, H, tot, g.sort_blocks, NB, bg_log2);
+    hipLaunchKernelGGL(sort_binscan_kernel, dim3((unsigned)cdiv(NB, 4), g.B), dim3(256), 0, s, H,
+                       tot, g.sort_blocks, NB);
     FK_HIP(hipGetLastError());
-    const size_t lds = (size_t)(NB + 40 + waves * NB) * sizeof(int);
-    hipLaunchKernelGGL(sort_scatter_kernel, grid, dim3(threads), lds, s, keys, vals_in, H, tot,
-                       vals_out, keys_out, seg_off, item_off, g.N, g.sort_tile, NB, shift, mask,
+    const size_t lds = (size_t)(NB + 40 + kSortWaves * NB) * sizeof(int);
+    hipLaunchKernelGGL(sort_scatter_kernel, grid, dim3(kSortThreads), lds, s, keys, vals_in, H,
+                       tot, vals_out, keys_out, seg_off, item_off, g.N, rounds, NB, shift, mask,
                        g.K - 1, nbits, g.rows_per_item);
     FK_HIP(hipGetLastError());
     return FK_OK;

@@ -119,48 +119,77 @@ __global__ __launch_bounds__(256) void segment_reduce_kernel(
     }
 }
 
-// One workgroup per cluster: s_k = sum of the cluster's item rows in item order,
-// n_k = seg_off[k+1] - seg_off[k].  Optionally added onto sums/counts already stored
+// One workgroup of 256 threads per cluster: s_k = sum of the cluster's item rows in a fixed
+// order, n_k = seg_off[k+1] - seg_off[k].  Optionally added onto sums/counts already stored
 // (chunked mode), optionally normalised into centroids (Algorithm 3, last loop; an empty
-// cluster keeps its previous centroid).
+// cluster keeps its previous centroid).  When c_frag is given, the rounded centroid is also
+// written in MFMA fragment order together with its score bias -||c||^2/2, so the next
+// assignment needs no separate re-layout pass.
 __global__ __launch_bounds__(256) void finalize_kernel(
     const float* __restrict__ partial, const int32_t* __restrict__ seg_off,
-    const int32_t* __restrict__ item_off, const float* C_prev,
-    float* C_out, uint16_t* __restrict__ C_lp_out, float* __restrict__ C_lp_f32_out,
-    int32_t* __restrict__ counts, float* __restrict__ sums, int d, int K, int64_t max_items,
+    const int32_t* __restrict__ item_off, const float* C_prev, float* C_out,
+    uint16_t* __restrict__ C_lp_out, float* __restrict__ C_lp_f32_out,
+    uint16_t* __restrict__ c_frag, float* __restrict__ c_bias, int32_t* __restrict__ counts,
+    float* __restrict__ sums, int d, int K, int64_t max_items, int ktiles, int dch,
     int accumulate, int normalise, int bf) {
-    __shared__ float red[256];
-    const int b = blockIdx.y, k = blockIdx.x;
+    __shared__ float red[1024];
+    __shared__ float nrm[128];
+    const int b = blockIdx.y, k = blockIdx.x, tid = threadIdx.x;
     seg_off += (size_t)b * (K + 1);
     item_off += (size_t)b * (K + 1);
-    const int T = blockDim.x;
-    // d <= 128 <= T: thread = (row slot, feature)
-    int dpow = 1;
+    int dpow = 4;
     while (dpow < d) dpow <<= 1;
-    const int slots = T / dpow, slot = threadIdx.x / dpow, j = threadIdx.x % dpow;
+    const int LR = dpow >> 2;                     // threads per row, 4 features each
+    const int slots = 256 / LR, slot = tid / LR, col = (tid % LR) * 4;
     const int i0 = item_off[k], i1 = item_off[k + 1];
     // read the running count before anyone overwrites it (barrier below)
     const int n_prev = accumulate ? counts[(size_t)b * K + k] : 0;
     const float* P = partial + (size_t)b * max_items * d;
-    float acc = 0.f;
-    if (j < d && slot < slots)
-        for (int it = i0 + slot; it < i1; it += slots) acc += P[(size_t)it * d + j];
-    red[threadIdx.x] = acc;
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    if (col < d)
+        for (int it = i0 + slot; it < i1; it += slots) acc += *(const floatx4*)(P + (size_t)it * d + col);
+    *(floatx4*)&red[slot * dpow + col] = acc;
     __syncthreads();
-    if (threadIdx.x < d) {
+    float c = 0.f;
+    uint16_t lp = 0;
+    int n = 0;
+    if (tid < d) {
         float s = 0.f;
-        for (int q = 0; q < slots; ++q) s += red[q * dpow + threadIdx.x];   // fixed order
-        const size_t o = ((size_t)b * K + k) * d + threadIdx.x;
-        const int n = seg_off[k + 1] - seg_off[k] + n_prev;
+        for (int q = 0; q < slots; ++q) s += red[q * dpow + tid];   // fixed order
+        const size_t o = ((size_t)b * K + k) * d + tid;
+        n = seg_off[k + 1] - seg_off[k] + n_prev;
         if (accumulate) s += sums[o];
         if (sums) sums[o] = s;
         if (normalise) {
-            const float c = n > 0 ? (float)((double)s / (double)n) : C_prev[o];
+            c = n > 0 ? (float)((double)s / (double)n) : C_prev[o];
             C_out[o] = c;
-            if (C_lp_out) C_lp_out[o] = float_to_lp(c, bf);
+            lp = float_to_lp(c, bf);
+            if (C_lp_out) C_lp_out[o] = lp;
             if (C_lp_f32_out) C_lp_f32_out[o] = c;
         }
-        if (threadIdx.x == 0) counts[(size_t)b * K + k] = n;
+        if (tid == 0) counts[(size_t)b * K + k] = n;
+    }
+    if (normalise && c_frag) {
+        // fragment order: tile k/32, chunk j/16, lane (j%16)/8*32 + k%32, element j%8
+        if (tid < d) {
+            const int j = tid;
+            const size_t pos = ((((size_t)b * ktiles + (k >> 5)) * dch + (j >> 4)) * 64 +
+                                (((j >> 3) & 1) << 5) + (k & 31)) * 8 + (j & 7);
+            c_frag[pos] = lp;
+            const float f = lp_to_float(lp, bf);
+            nrm[tid] = __fmul_rn(f, f);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            // same association as the stand-alone layout kernel: groups of 8 features first
+            float n2 = 0.f;
+            for (int g0 = 0; g0 < d; g0 += 8) {
+                float ss = 0.f;
+                for (int e = 0; e < 8; ++e) ss = __fadd_rn(ss, nrm[g0 + e]);
+                n2 = __fadd_rn(n2, ss);
+            }
+            c_bias[((size_t)b * ktiles) * 32 + k] = -0.5f * n2;
+        }
     }
 }
 
@@ -195,15 +224,14 @@ fk_status launch_segment_reduce(const Geometry& g, const Workspace& w, const voi
 
 fk_status launch_finalize(const Geometry& g, const Workspace& w, const int32_t* seg_off,
                           const int32_t* item_off, const FinalizeArgs& a, hipStream_t s) {
-    // few large clusters: more row slots per workgroup
-    const int threads = (g.max_items / g.K >= 8) ? 256 : 128;
     uint16_t* lp16 = g.t == FK_F32 ? nullptr : (uint16_t*)a.C_out_lp;
     float* lp32 = g.t == FK_F32 ? (float*)a.C_out_lp : nullptr;
     if (lp32 == a.C_out_f32) lp32 = nullptr;
-    hipLaunchKernelGGL(finalize_kernel, dim3(g.K, g.B), dim3(threads), 0, s, w.partial, seg_off,
-                       item_off, a.C_prev_f32, a.C_out_f32, lp16, lp32, a.counts, a.sums, g.d, g.K,
-                       g.max_items, a.accumulate ? 1 : 0, a.normalise ? 1 : 0,
-                       g.t == FK_BF16 ? 1 : 0);
+    uint16_t* frag = g.t == FK_F32 ? nullptr : (uint16_t*)a.c_frag;
+    hipLaunchKernelGGL(finalize_kernel, dim3(g.K, g.B), dim3(256), 0, s, w.partial, seg_off,
+                       item_off, a.C_prev_f32, a.C_out_f32, lp16, lp32, frag, a.c_bias, a.counts,
+                       a.sums, g.d, g.K, g.max_items, g.ktiles, g.dchunks, a.accumulate ? 1 : 0,
+                       a.normalise ? 1 : 0, g.t == FK_BF16 ? 1 : 0);
     FK_HIP(hipGetLastError());
     return FK_OK;
 }
