@@ -1,0 +1,108 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The oracle cannot redo a full-size problem in seconds, so each case checks
+  * assignments of a seeded sample of points, one by one, against the oracle (same rule
+    as the small cases),
+  * the update of a seeded sample of whole clusters against the oracle's mean of the
+    members the GPU assigned to them,
+  * properties that hold at any size: counts equal the histogram of the assignments and
+    sum to N, every index is in range, X is left untouched.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2603_09229_amd import binding as fk
+from paper_2603_09229_amd import workloads as wl
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+DEV = torch.device("cuda:0")
+
+
+def _checksum(X: torch.Tensor) -> int:
+    return int(X.view(torch.int16).to(torch.int64).sum()) if X.element_size() == 2 \
+        else int(X.view(torch.int32).to(torch.int64).sum())
+
+
+def _check_instance(w, Xb, consumed_b, C_prev_b, C_new_b, a_b, counts_b, n_points, n_clusters, seed):
+    """Xb [N,d] device, consumed_b [K,d] device (kernel dtype), a_b [N], counts_b [K]."""
+    g = torch.Generator().manual_seed(seed)
+    N, K = Xb.shape[0], consumed_b.shape[0]
+    assert int(a_b.min()) >= 0 and int(a_b.max()) < K
+    hist = torch.bincount(a_b.to(torch.int64), minlength=K)
+    assert torch.equal(hist, counts_b.to(torch.int64)) and int(hist.sum()) == N
+    # sampled points, all K centroids
+    pick = torch.randint(0, N, (n_points,), generator=g).to(Xb.device)
+    Xs = parity.widen(Xb[pick])
+    st = parity.check_assign(Xs, parity.widen(consumed_b), a_b[pick].cpu().numpy())
+    # sampled clusters, all their members (non-empty ones and, if any, an empty one)
+    tol = parity.CENTROID_TOL[w.torch_dtype]
+    ks = torch.randint(0, K, (n_clusters,), generator=g).tolist()
+    ks.append(int(hist.argmax()))
+    empties = torch.nonzero(hist == 0).flatten()
+    if empties.numel():
+        ks.append(int(empties[0]))
+    for k in set(ks):
+        members = torch.nonzero(a_b == k).flatten()
+        if members.numel() == 0:
+            assert torch.equal(C_new_b[k], C_prev_b[k])
+            continue
+        Xm = parity.widen(Xb[members])
+        u = oracle.update(Xm, np.zeros(len(Xm), np.int32), C_prev_b[k:k + 1].cpu().numpy())
+        assert int(u["counts"][0]) == int(counts_b[k])
+        parity.check_centroids(C_new_b[k:k + 1].cpu().numpy(), u["C"], tol, f"cluster {k}")
+    return st
+
+
+def _run_incore(w, n_points, n_clusters, instances, iters=2):
+    X, lab = wl.make_points(w, device=DEV, return_labels=True)
+    idx = wl.init_rows(w, lab if w.zipf_s > 0 else None)
+    del lab
+    C = wl.gather_rows(X, idx).contiguous()
+    before = _checksum(X)
+    ws = fk.make_workspace(w.B, w.N, w.d, w.K, w.torch_dtype, DEV)
+    for it in range(iters):
+        C_prev = C.clone()
+        consumed = C_prev.to(w.torch_dtype)
+        a, counts, C_lp = fk.fk_lloyd_iter(X, C, 1, ws=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(C_lp, C.to(w.torch_dtype))
+        for b in instances:
+            st = _check_instance(w, X[b], consumed[b], C_prev[b], C[b], a[b], counts[b],
+                                 n_points, n_clusters, seed=17 * it + b)
+            print(f"{w.name} iter {it} instance {b}: {st}", flush=True)
+    assert _checksum(X) == before
+
+
+def test_c2_full_size():
+    _run_incore(wl.C2, n_points=4096, n_clusters=24, instances=[0])
+
+
+def test_c3_full_size_batched():
+    _run_incore(wl.C3, n_points=2048, n_clusters=12, instances=[0, 13, 31])
+
+
+def test_c4_full_size_skewed():
+    _run_incore(wl.C4, n_points=8192, n_clusters=4, instances=[0])
+
+
+def test_c5_recipe_out_of_core_large_k():
+    """The out-of-core configuration's recipe (K = 65536, d = 128, fp16, X in pinned host
+    memory, streamed in chunks) at N = 2^22 so the host buffer stays at 1 GiB."""
+    w = wl.C5.scaled(N=1 << 22)
+    Xh = torch.empty((1, w.N, w.d), dtype=w.torch_dtype, pin_memory=True)
+    Xd = wl.make_points(w, device=DEV, rows_per_block=1 << 20)
+    Xh.copy_(Xd)
+    idx = wl.init_rows(w)
+    C = wl.gather_rows(Xd, idx)[0].contiguous()
+    chunk = 1 << 20
+    dev_ws = torch.empty(fk.fk_ooc_workspace_bytes(chunk, w.d, w.K, w.torch_dtype),
+                         dtype=torch.uint8, device=DEV)
+    for it in range(2):
+        C_prev = C.clone()
+        consumed = C_prev.to(w.torch_dtype)
+        a, counts = fk.fk_lloyd_ooc(Xh[0], C, 1, dev_ws=dev_ws, chunk_rows=chunk)
+        st = _check_instance(w, Xd[0], consumed, C_prev, C, a, counts, 1024, 48, seed=it)
+        print(f"{w.name} (N=2^22) iter {it}: {st}", flush=True)
