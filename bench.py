@@ -48,6 +48,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy first (reference for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -70,6 +73,14 @@ def main() -> int:
     steps = args.steps if args.steps is not None else w.iters
     if args.workload == "c5":
         return bench_ooc(args, w, steps, torch, fk, wl, dev)
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)          # 1 GiB read + 1 GiB written per launch
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---------------------------------------------------------------- inputs (synthetic)
     X, lab = wl.make_points(w, device=dev, return_labels=True)
