@@ -201,31 +201,40 @@ def cpu_baseline(w, X, C0, torch):
 
 
 def bench_ooc(args, w, steps, torch, fk, wl, dev):
-    """Out-of-core configuration: X in pinned host memory, streamed in chunks."""
+    """Out-of-core configuration: X in pinned host memory, streamed in 2^24-row chunks through
+    a device working set capped at 32 GB.  FK_OOC_ROWS overrides N (smaller boxes)."""
     cap = 32 << 30
     N = int(os.environ.get("FK_OOC_ROWS", w.N))
     w = w.scaled(N=N)
+    t0 = time.perf_counter()
     Xh = torch.empty((1, w.N, w.d), dtype=w.torch_dtype, pin_memory=True)
+    print(f"pinned {Xh.numel() * 2 / 2**30:.1f} GiB in {time.perf_counter() - t0:.1f} s",
+          file=sys.stderr, flush=True)
+    # workloads.make_points generates on the GPU block by block and copies each block down
+    g = torch.Generator(device=dev)
+    g.manual_seed(w.seed)
+    centres = torch.randn((w.K, w.d), generator=g, device=dev) * w.center_std
     blk = 1 << 24
-    # same recipe as workloads.make_points, generated on the GPU block by block and copied
-    # down into the pinned buffer
-    torch.manual_seed(w.seed)
-    centres = torch.randn((w.K, w.d), device=dev) * w.center_std
     for r0 in range(0, w.N, blk):
         r1 = min(w.N, r0 + blk)
-        lab = torch.randint(0, w.K, (r1 - r0,), device=dev)
-        x = torch.randn((r1 - r0, w.d), device=dev).mul_(w.noise_std).add_(centres[lab])
+        lab = torch.randint(0, w.K, (r1 - r0,), generator=g, device=dev)
+        x = torch.randn((r1 - r0, w.d), generator=g, device=dev).mul_(w.noise_std).add_(centres[lab])
         Xh[0, r0:r1].copy_(x.to(w.torch_dtype))
-    del x, lab
+        del x, lab
+    print(f"generated in {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
     idx = torch.randint(0, w.N, (w.K,), generator=torch.Generator().manual_seed(w.seed + 1000))
     C = Xh[0][idx].to(torch.float32).to(dev).contiguous()
-    dev_ws = torch.empty(cap - (1 << 30), dtype=torch.uint8, device=dev)
+    chunk = min(1 << 24, w.N)
+    need = fk.fk_ooc_workspace_bytes(chunk, w.d, w.K, w.torch_dtype)
+    assert 0 < need <= cap - (1 << 30), need
+    dev_ws = torch.empty(need, dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
     if args.warmup > 0:
-        fk.fk_lloyd_ooc(Xh[0], C, 1, dev_ws=dev_ws, keep_assign=False)
-    t0 = time.perf_counter()
-    a, counts = fk.fk_lloyd_ooc(Xh[0], C, steps, dev_ws=dev_ws, keep_assign=False)
-    elapsed = time.perf_counter() - t0
+        fk.fk_lloyd_ooc(Xh[0], C, 1, dev_ws=dev_ws, chunk_rows=chunk, keep_assign=False)
+    print(f"warm-up done at {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
+    t1 = time.perf_counter()
+    a, counts = fk.fk_lloyd_ooc(Xh[0], C, steps, dev_ws=dev_ws, chunk_rows=chunk, keep_assign=False)
+    elapsed = time.perf_counter() - t1
     assert int(counts.sum()) == w.N
     ms = elapsed * 1e3 / steps
     flops = 2.0 * w.N * w.K * w.d
@@ -235,12 +244,14 @@ def bench_ooc(args, w, steps, torch, fk, wl, dev):
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
            "data": "synthetic",
            "config": {"workload": w.name, "B": 1, "N": w.N, "d": w.d, "K": w.K,
-                      "storage": w.dtype, "device_cap_bytes": cap, "x": "pinned host"},
+                      "storage": w.dtype, "chunk_rows": chunk, "device_workspace_bytes": need,
+                      "device_cap_bytes": cap, "x": "pinned host memory"},
            "end_to_end_tflops": tf,
+           "host_to_device_gbps": w.N * w.d * 2 / (ms * 1e-3) / 1e9,
            "roofline": {"kernel": "assign_mfma_kernel", "bound": "mfma", "achieved": tf,
                         "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
                         "frac": tf / PEAK_MFMA_F16_TFLOPS, "traffic": None,
-                        "note": "whole iteration incl. PCIe streaming, not the kernel alone"}}
+                        "note": "whole iteration including the PCIe stream, not the kernel alone"}}
     print(json.dumps(out))
     return 0
 

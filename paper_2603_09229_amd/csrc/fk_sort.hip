@@ -20,10 +20,14 @@ __device__ __forceinline__ int clamp_key(int k, int kmax) { return min(max(k, 0)
 // Lanes of the wave whose `digit` equals this lane's, among lanes in `valid`.
 __device__ __forceinline__ uint64_t match_digit(int digit, int nbits, uint64_t valid) {
     uint64_t peers = valid;
-    for (int b = 0; b < nbits; ++b) {
-        const bool bit = (digit >> b) & 1;
-        const uint64_t bal = __ballot(bit);
-        peers &= bit ? bal : ~bal;
+    // digits have at most 11 bits; unrolled, each step guarded by a wave-uniform test
+#pragma unroll
+    for (int b = 0; b < 11; ++b) {
+        if (b < nbits) {
+            const bool bit = (digit >> b) & 1;
+            const uint64_t bal = __ballot(bit);
+            peers &= bit ? bal : ~bal;
+        }
     }
     return peers;
 }
@@ -67,16 +71,15 @@ __device__ int block_exclusive_scan(int* v, int n, int* scratch) {
 }  // namespace
 
 // ------------------------------------------------------------------------------------
-// Tiling shared by the histogram and scatter kernels: a workgroup of 256 threads owns
-// `rounds` consecutive sub-tiles of 4096 keys; inside a sub-tile wave w owns keys
-// [w*1024, (w+1)*1024) as 16 batches of 64, batch j at offset j*64 + lane.  All 16 loads of
-// a round are issued before any is used.
-constexpr int kSortThreads = 256;
-constexpr int kSortWaves = 4;
-constexpr int kBatches = 16;                 // batches of 64 keys per wave per round
-constexpr int kSubTile = kSortWaves * kBatches * 64;   // 4096
+// Tiling shared by the histogram and scatter kernels: a workgroup of WAVES waves (8, or 4
+// when the per-wave counters of a wide digit would not fit in LDS) owns `rounds` consecutive
+// sub-tiles of 4096 keys; inside a sub-tile wave w owns 4096/WAVES consecutive keys as
+// batches of 64, batch j at offset j*64 + lane.  All loads of a round are issued before any
+// is used.
+constexpr int kSubTile = 4096;
 
 // Keys come back clamped to [0, kmax]; -1 marks a lane past the end of the array.
+template <int kBatches>
 __device__ __forceinline__ void load_round(const int32_t* __restrict__ keys, int64_t base,
                                            int64_t N, int lane, int kmax, int (&k)[kBatches]) {
 #pragma unroll
@@ -92,9 +95,11 @@ __device__ __forceinline__ void load_round(const int32_t* __restrict__ keys, int
 }
 
 // Per-workgroup digit histogram, written transposed: H[b][bin][blk].
-__global__ __launch_bounds__(kSortThreads) void sort_hist_kernel(
+template <int kSortWaves>
+__global__ __launch_bounds__(kSortWaves * 64) void sort_hist_kernel(
     const int32_t* __restrict__ keys, int32_t* __restrict__ H, int64_t N, int rounds, int NB,
     int shift, int mask, int kmax) {
+    constexpr int kSortThreads = kSortWaves * 64, kBatches = kSubTile / kSortThreads;
     extern __shared__ int lds[];
     int* hist = lds;
     const int b = blockIdx.y, blk = blockIdx.x, nb = gridDim.x;
@@ -161,12 +166,14 @@ __global__ __launch_bounds__(256) void sort_binscan_kernel(int32_t* __restrict__
 //   vals_in == NULL: values are the key positions (first pass).
 //   keys_out may be NULL.  seg_off / item_off are written by workgroup 0 when non-NULL
 //   (single-pass sort: bins are cluster ids, so the bin offsets are the segment table).
-__global__ __launch_bounds__(kSortThreads) void sort_scatter_kernel(
+template <int kSortWaves>
+__global__ __launch_bounds__(kSortWaves * 64) void sort_scatter_kernel(
     const int32_t* __restrict__ keys, const int32_t* __restrict__ vals_in,
     const int32_t* __restrict__ H, const int32_t* __restrict__ tot,
     int32_t* __restrict__ vals_out, int32_t* __restrict__ keys_out,
     int32_t* __restrict__ seg_off, int32_t* __restrict__ item_off, int64_t N, int rounds,
     int NB, int shift, int mask, int kmax, int nbits, int R) {
+    constexpr int kSortThreads = kSortWaves * 64, kBatches = kSubTile / kSortThreads;
     extern __shared__ int lds[];
     int* off = lds;                    // [NB]
     int* scratch = off + NB;           // [40]
@@ -330,16 +337,27 @@ static fk_status sort_pass(const Geometry& g, const Workspace& w, const int32_t*
     int32_t* H = w.block_hist;
     int32_t* tot = w.digit_off;
     dim3 grid(g.sort_blocks, g.B);
-    hipLaunchKernelGGL(sort_hist_kernel, grid, dim3(kSortThreads), NB * sizeof(int), s, keys, H,
-                       g.N, rounds, NB, shift, mask, g.K - 1);
+    const bool wide = NB > 1024;       // 8 waves of counters would not fit in LDS
+    if (wide)
+        hipLaunchKernelGGL(sort_hist_kernel<4>, grid, dim3(256), NB * sizeof(int), s, keys, H, g.N,
+                           rounds, NB, shift, mask, g.K - 1);
+    else
+        hipLaunchKernelGGL(sort_hist_kernel<8>, grid, dim3(512), NB * sizeof(int), s, keys, H, g.N,
+                           rounds, NB, shift, mask, g.K - 1);
     FK_HIP(hipGetLastError());
     hipLaunchKernelGGL(sort_binscan_kernel, dim3((unsigned)cdiv(NB, 4), g.B), dim3(256), 0, s, H,
                        tot, g.sort_blocks, NB);
     FK_HIP(hipGetLastError());
-    const size_t lds = (size_t)(NB + 40 + kSortWaves * NB) * sizeof(int);
-    hipLaunchKernelGGL(sort_scatter_kernel, grid, dim3(kSortThreads), lds, s, keys, vals_in, H,
-                       tot, vals_out, keys_out, seg_off, item_off, g.N, rounds, NB, shift, mask,
-                       g.K - 1, nbits, g.rows_per_item);
+    const int waves = wide ? 4 : 8;
+    const size_t lds = (size_t)(NB + 40 + waves * NB) * sizeof(int);
+    if (wide)
+        hipLaunchKernelGGL(sort_scatter_kernel<4>, grid, dim3(256), lds, s, keys, vals_in, H, tot,
+                           vals_out, keys_out, seg_off, item_off, g.N, rounds, NB, shift, mask,
+                           g.K - 1, nbits, g.rows_per_item);
+    else
+        hipLaunchKernelGGL(sort_scatter_kernel<8>, grid, dim3(512), lds, s, keys, vals_in, H, tot,
+                           vals_out, keys_out, seg_off, item_off, g.N, rounds, NB, shift, mask,
+                           g.K - 1, nbits, g.rows_per_item);
     FK_HIP(hipGetLastError());
     return FK_OK;
 }
