@@ -80,8 +80,11 @@ bool make_geometry(int B, int64_t N, int d, int K, fk_dtype t, Geometry* g) {
     int64_t T = 4096 * cdiv(N, (int64_t)4096 * 4096);
     g->sort_tile = (int)T;
     g->sort_blocks = (int)cdiv(N, T);
-    int64_t R = cdiv(N, 4096);
-    if (R < 256) R = 256;
+    // rows reduced into one partial row: 256 by one wave, or, for N above 4M points, N/4096 by
+    // the four waves of a workgroup (at most ~4096 + K partial rows to merge afterwards)
+    int64_t R = 256;
+    g->waves_per_item = 1;
+    if (N > ((int64_t)1 << 22)) { R = cdiv(N, 4096); g->waves_per_item = 4; }
     g->rows_per_item = (int)R;
     g->max_items = N / R + K;
     return true;

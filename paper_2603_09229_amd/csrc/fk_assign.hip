@@ -320,8 +320,8 @@ __global__ __launch_bounds__(WAVES * 64) void assign_mfma_kernel(
 // ------------------------------------------------------------------------------------
 // fp32: one point per thread, features in registers, centroid tiles of TK rows in LDS,
 // D_ik by direct differences in fp32; ascending k with strict '<'.
-template <int DMAX, int TK>
-__global__ __launch_bounds__(256) void assign_f32_kernel(
+template <int DMAX, int TK, int THREADS>
+__global__ __launch_bounds__(THREADS) void assign_f32_kernel(
     const float* __restrict__ X, const float* __restrict__ C, int32_t* __restrict__ assign,
     float* __restrict__ min_dist, int64_t N, int d, int K) {
     __shared__ float sc[TK][DMAX];
@@ -330,7 +330,7 @@ __global__ __launch_bounds__(256) void assign_f32_kernel(
     C += (size_t)b * K * d;
     assign += (size_t)b * N;
     if (min_dist) min_dist += (size_t)b * N;
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t i = (int64_t)blockIdx.x * THREADS + threadIdx.x;
     float x[DMAX];
 #pragma unroll
     for (int j = 0; j < DMAX; j += 4) {
@@ -342,7 +342,7 @@ __global__ __launch_bounds__(256) void assign_f32_kernel(
     int a = 0;
     for (int k0 = 0; k0 < K; k0 += TK) {
         __syncthreads();
-        for (int o = threadIdx.x; o < TK * DMAX; o += 256) {
+        for (int o = threadIdx.x; o < TK * DMAX; o += THREADS) {
             const int r = o / DMAX, j = o % DMAX;
             sc[r][j] = (k0 + r < K && j < d) ? C[(size_t)(k0 + r) * d + j] : 0.f;
         }
@@ -363,6 +363,72 @@ __global__ __launch_bounds__(256) void assign_f32_kernel(
     if (i < N) {
         assign[i] = a;
         if (min_dist) min_dist[i] = m;
+    }
+}
+
+// Small fp32 problems: 64 points per workgroup, the four waves split every 32-row centroid
+// tile between them (8 rows each), then the four candidates of a point are merged through
+// LDS (smaller distance first, lower index on equal distances).  Four times the parallelism
+// of the one-thread-per-point kernel when there are too few points to fill the chip.
+template <int DMAX>
+__global__ __launch_bounds__(256) void assign_f32_split_kernel(
+    const float* __restrict__ X, const float* __restrict__ C, int32_t* __restrict__ assign,
+    float* __restrict__ min_dist, int64_t N, int d, int K) {
+    constexpr int TK = 32;
+    __shared__ float sc[TK][DMAX];
+    __shared__ float cand_d[4][64];
+    __shared__ int cand_k[4][64];
+    const int b = blockIdx.y;
+    X += (size_t)b * N * d;
+    C += (size_t)b * K * d;
+    assign += (size_t)b * N;
+    if (min_dist) min_dist += (size_t)b * N;
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int64_t i = (int64_t)blockIdx.x * 64 + lane;
+    float x[DMAX];
+#pragma unroll
+    for (int j = 0; j < DMAX; j += 4) {
+        floatx4 v = {0.f, 0.f, 0.f, 0.f};
+        if (i < N && j < d) v = *(const floatx4*)(X + (size_t)i * d + j);
+        x[j] = v[0]; x[j + 1] = v[1]; x[j + 2] = v[2]; x[j + 3] = v[3];
+    }
+    float m = INFINITY;
+    int a = 0x7FFFFFFF;
+    for (int k0 = 0; k0 < K; k0 += TK) {
+        __syncthreads();
+        for (int o = threadIdx.x; o < TK * DMAX; o += 256) {
+            const int r = o / DMAX, j = o % DMAX;
+            sc[r][j] = (k0 + r < K && j < d) ? C[(size_t)(k0 + r) * d + j] : 0.f;
+        }
+        __syncthreads();
+        for (int rr = 0; rr < 8; ++rr) {
+            const int r = q * 8 + rr;
+            if (k0 + r >= K) break;
+            float D = 0.f;
+#pragma unroll
+            for (int j = 0; j < DMAX; j += 4) {
+                const floatx4 c = *(const floatx4*)&sc[r][j];
+                const float e0 = x[j] - c[0], e1 = x[j + 1] - c[1];
+                const float e2 = x[j + 2] - c[2], e3 = x[j + 3] - c[3];
+                D += e0 * e0; D += e1 * e1; D += e2 * e2; D += e3 * e3;
+            }
+            if (D < m) { m = D; a = k0 + r; }
+        }
+    }
+    cand_d[q][lane] = m;
+    cand_k[q][lane] = a;
+    __syncthreads();
+    if (q == 0 && i < N) {
+        float bm = cand_d[0][lane];
+        int bk = cand_k[0][lane];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            const float dm = cand_d[w][lane];
+            const int dk = cand_k[w][lane];
+            if (dm < bm || (dm == bm && dk < bk)) { bm = dm; bk = dk; }
+        }
+        assign[i] = min(bk, K - 1);
+        if (min_dist) min_dist[i] = bm;
     }
 }
 
@@ -420,15 +486,25 @@ fk_status launch_assign(const Geometry& g, const void* X, const void* C_or_frag,
                         const float* c_bias, int32_t* assign, float* min_dist, hipStream_t s) {
     if (g.t == FK_F16) return launch_mfma_d<false>(g, X, C_or_frag, c_bias, assign, min_dist, s);
     if (g.t == FK_BF16) return launch_mfma_d<true>(g, X, C_or_frag, c_bias, assign, min_dist, s);
-    dim3 grid((unsigned)cdiv(g.N, 256), g.B), block(256);
+    // small problems: split each centroid tile over the waves, so that even 16K points spread
+    // over the chip
     const float* Xf = (const float*)X;
     const float* Cf = (const float*)C_or_frag;
-    if (g.d <= 32)
-        hipLaunchKernelGGL((assign_f32_kernel<32, 32>), grid, block, 0, s, Xf, Cf, assign, min_dist, g.N, g.d, g.K);
-    else if (g.d <= 64)
-        hipLaunchKernelGGL((assign_f32_kernel<64, 32>), grid, block, 0, s, Xf, Cf, assign, min_dist, g.N, g.d, g.K);
-    else
-        hipLaunchKernelGGL((assign_f32_kernel<128, 32>), grid, block, 0, s, Xf, Cf, assign, min_dist, g.N, g.d, g.K);
+    const bool small = (int64_t)g.B * g.N < ((int64_t)1 << 18);
+    dim3 grid((unsigned)cdiv(g.N, small ? 64 : 256), g.B), block(256);
+#define FK_F32_LAUNCH(DM)                                                                         \
+    do {                                                                                          \
+        if (small)                                                                                \
+            hipLaunchKernelGGL((assign_f32_split_kernel<DM>), grid, block, 0, s, Xf, Cf, assign,  \
+                               min_dist, g.N, g.d, g.K);                                          \
+        else                                                                                      \
+            hipLaunchKernelGGL((assign_f32_kernel<DM, 32, 256>), grid, block, 0, s, Xf, Cf, assign, \
+                               min_dist, g.N, g.d, g.K);                                          \
+    } while (0)
+    if (g.d <= 32) FK_F32_LAUNCH(32);
+    else if (g.d <= 64) FK_F32_LAUNCH(64);
+    else FK_F32_LAUNCH(128);
+#undef FK_F32_LAUNCH
     FK_HIP(hipGetLastError());
     return FK_OK;
 }

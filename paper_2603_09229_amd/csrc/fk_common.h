@@ -46,7 +46,8 @@ struct Geometry {
     int sort_tile;    // keys per sort workgroup
     int sort_blocks;  // workgroups per instance = ceil(N / sort_tile)
     // segment reduction
-    int rows_per_item;   // R: sorted positions one wave reduces
+    int rows_per_item;   // R: sorted positions reduced into one partial row
+    int waves_per_item;  // 1, or 4 (a whole workgroup) for the long items of few-cluster shapes
     int64_t max_items;   // upper bound on sum_k ceil(n_k / R) per instance
 };
 

@@ -98,7 +98,7 @@ __device__ __forceinline__ void load_round(const int32_t* __restrict__ keys, int
 template <int kSortWaves>
 __global__ __launch_bounds__(kSortWaves * 64) void sort_hist_kernel(
     const int32_t* __restrict__ keys, int32_t* __restrict__ H, int64_t N, int rounds, int NB,
-    int shift, int mask, int kmax) {
+    int shift, int mask, int kmax, int nbits) {
     constexpr int kSortThreads = kSortWaves * 64, kBatches = kSubTile / kSortThreads;
     extern __shared__ int lds[];
     int* hist = lds;
@@ -107,58 +107,75 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_hist_kernel(
     keys += (size_t)b * N;
     for (int i = tid; i < NB; i += kSortThreads) hist[i] = 0;
     __syncthreads();
-    int mine = 0;                              // small NB: lane b counts bin b for its wave
+    // rounds are software-pipelined: the next round's keys are requested before this round's
+    // are counted
+    const int64_t base0 = (int64_t)blk * rounds * kSubTile + wave * (kBatches * 64);
+    int k[kBatches], kn[kBatches];
+    load_round(keys, base0, N, lane, kmax, k);
     for (int r = 0; r < rounds; ++r) {
-        const int64_t base = ((int64_t)blk * rounds + r) * kSubTile + wave * (kBatches * 64);
-        if (base >= N) break;
-        int k[kBatches];
-        load_round(keys, base, N, lane, kmax, k);
-        if (NB <= 32) {
-            // hot bins would serialise LDS atomics: count with ballots instead
+        const int64_t nbase = base0 + (int64_t)(r + 1) * kSubTile;
+        const bool more = r + 1 < rounds && nbase < N;
+        if (more) load_round(keys, nbase, N, lane, kmax, kn);
+        if (NB <= 64) {
+            // hot bins would serialise per-key LDS atomics: one add per distinct digit and batch
 #pragma unroll
             for (int j = 0; j < kBatches; ++j) {
-                const int digit = k[j] < 0 ? -1 : (k[j] >> shift) & mask;
-                for (int bin = 0; bin < NB; ++bin) {
-                    const int c = __popcll(__ballot(digit == bin));
-                    if (lane == bin) mine += c;
-                }
+                const bool valid = k[j] >= 0;
+                const int digit = valid ? (k[j] >> shift) & mask : 0;
+                const uint64_t peers = match_digit(digit, nbits, __ballot(valid));
+                if (valid && (peers & lanemask_lt()) == 0) atomicAdd(&hist[digit], __popcll(peers));
             }
         } else {
 #pragma unroll
             for (int j = 0; j < kBatches; ++j)
                 if (k[j] >= 0) atomicAdd(&hist[(k[j] >> shift) & mask], 1);
         }
+        if (!more) break;
+#pragma unroll
+        for (int j = 0; j < kBatches; ++j) k[j] = kn[j];
     }
-    if (NB <= 32 && lane < NB && mine) atomicAdd(&hist[lane], mine);
     __syncthreads();
     int32_t* out = H + (size_t)b * NB * nb + blk;
     for (int i = tid; i < NB; i += kSortThreads) out[(size_t)i * nb] = hist[i];
 }
 
-// Exclusive scan of H[b][bin][0..nb) in place, one wave per bin; tot[b][bin] = row sum.
+// Exclusive scan of H[b][bin][0..nb) in place; tot[b][bin] = row sum.  TPB threads (one wave,
+// or the whole workgroup for long rows) share a bin, each owning a contiguous run of entries.
+template <int TPB>
 __global__ __launch_bounds__(256) void sort_binscan_kernel(int32_t* __restrict__ H,
                                                            int32_t* __restrict__ tot, int nb,
                                                            int NB) {
-    const int b = blockIdx.y, lane = threadIdx.x & 63;
-    const int bin = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (bin >= NB) return;
-    int32_t* row = H + ((size_t)b * NB + bin) * nb;
-    const int per = (nb + 63) >> 6;
-    const int lo = min(nb, lane * per), hi = min(nb, lo + per);
+    __shared__ int wsum[4];
+    const int b = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int bin = TPB == 64 ? blockIdx.x * 4 + wave : blockIdx.x;
+    const int t = TPB == 64 ? lane : threadIdx.x;          // index inside the bin's team
+    const bool live = bin < NB;
+    int32_t* row = H + ((size_t)b * NB + (live ? bin : 0)) * nb;
+    const int per = (nb + TPB - 1) / TPB;
+    const int lo = live ? min(nb, t * per) : 0, hi = live ? min(nb, lo + per) : 0;
     int sum = 0;
     for (int i = lo; i < hi; ++i) sum += row[i];
     int inc = sum;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
-        const int t = __shfl_up(inc, o);
-        if (lane >= o) inc += t;
+        const int v = __shfl_up(inc, o);
+        if (lane >= o) inc += v;
     }
-    if (lane == 63) tot[(size_t)b * NB + bin] = inc;
-    int run = inc - sum;
+    int base = 0, total = inc;                             // total valid in lane 63
+    if (TPB == 256) {
+        if (lane == 63) wsum[wave] = inc;
+        __syncthreads();
+        for (int w = 0; w < wave; ++w) base += wsum[w];
+        total = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+        if (live && threadIdx.x == 0) tot[(size_t)b * NB + bin] = total;
+    } else if (live && lane == 63) {
+        tot[(size_t)b * NB + bin] = total;
+    }
+    int run = base + inc - sum;
     for (int i = lo; i < hi; ++i) {
-        const int t = row[i];
+        const int v = row[i];
         row[i] = run;
-        run += t;
+        run += v;
     }
 }
 
@@ -340,13 +357,17 @@ static fk_status sort_pass(const Geometry& g, const Workspace& w, const int32_t*
     const bool wide = NB > 1024;       // 8 waves of counters would not fit in LDS
     if (wide)
         hipLaunchKernelGGL(sort_hist_kernel<4>, grid, dim3(256), NB * sizeof(int), s, keys, H, g.N,
-                           rounds, NB, shift, mask, g.K - 1);
+                           rounds, NB, shift, mask, g.K - 1, nbits);
     else
         hipLaunchKernelGGL(sort_hist_kernel<8>, grid, dim3(512), NB * sizeof(int), s, keys, H, g.N,
-                           rounds, NB, shift, mask, g.K - 1);
+                           rounds, NB, shift, mask, g.K - 1, nbits);
     FK_HIP(hipGetLastError());
-    hipLaunchKernelGGL(sort_binscan_kernel, dim3((unsigned)cdiv(NB, 4), g.B), dim3(256), 0, s, H,
-                       tot, g.sort_blocks, NB);
+    if (g.sort_blocks > 512)
+        hipLaunchKernelGGL(sort_binscan_kernel<256>, dim3((unsigned)NB, g.B), dim3(256), 0, s, H,
+                           tot, g.sort_blocks, NB);
+    else
+        hipLaunchKernelGGL(sort_binscan_kernel<64>, dim3((unsigned)cdiv(NB, 4), g.B), dim3(256), 0,
+                           s, H, tot, g.sort_blocks, NB);
     FK_HIP(hipGetLastError());
     const int waves = wide ? 4 : 8;
     const size_t lds = (size_t)(NB + 40 + waves * NB) * sizeof(int);

@@ -48,21 +48,26 @@ __device__ __forceinline__ int find_cluster(const int32_t* __restrict__ item_off
 
 }  // namespace
 
-// One wave per item.  EPL elements of 16 bytes per lane (8 for 16-bit types, 4 for fp32);
-// 2^lpr_log2 lanes span a row, so a wave reads 64 >> lpr_log2 rows per load instruction.
-template <int EPL, bool BF>
+// WPI waves per item (1, or all 4 of the workgroup for the long items of few-cluster
+// shapes).  EPL elements of 16 bytes per lane (8 for 16-bit types, 4 for fp32); 2^lpr_log2
+// lanes span a row, so a wave reads 64 >> lpr_log2 rows per load instruction.  With WPI = 4
+// wave w takes the 64-row batches w, w+4, ... of the item and the four wave sums are added in
+// wave order through LDS.
+template <int EPL, bool BF, int WPI>
 __global__ __launch_bounds__(256) void segment_reduce_kernel(
     const void* __restrict__ Xv, const int32_t* __restrict__ sorted_idx,
     const int32_t* __restrict__ seg_off, const int32_t* __restrict__ item_off,
     float* __restrict__ partial, int64_t N, int d, int K, int R, int64_t max_items,
     int lpr_log2) {
+    __shared__ float wsum[4][128];
     const int b = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t item = (int64_t)blockIdx.x * 4 + wave;
+    const int64_t item = WPI == 4 ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave;
+    const int part = WPI == 4 ? wave : 0;          // which share of the item this wave takes
     seg_off += (size_t)b * (K + 1);
     item_off += (size_t)b * (K + 1);
     sorted_idx += (size_t)b * N;
-    if (item >= item_off[K]) return;   // wave-uniform
+    if (item >= item_off[K]) return;   // uniform over the waves that share an item
     const int k = find_cluster(item_off, K, (int)item, lane);
     const int piece = (int)item - item_off[k];
     const int start = seg_off[k] + piece * R;
@@ -76,8 +81,8 @@ __global__ __launch_bounds__(256) void segment_reduce_kernel(
 #pragma unroll
     for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
 
-    constexpr int U = 4;
-    for (int r0 = start; r0 < end; r0 += 64) {
+    constexpr int U = 8;
+    for (int r0 = start + part * 64; r0 < end; r0 += 64 * WPI) {
         const int nrows = min(64, end - r0);
         const int myidx = lane < nrows ? sorted_idx[r0 + lane] : 0;
         for (int q = 0; q < nrows; q += S * U) {
@@ -85,8 +90,8 @@ __global__ __launch_bounds__(256) void segment_reduce_kernel(
             bool ok[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int rr = q + u * S + slot;              // < 64 always
-                const int idx = __shfl(myidx, rr);
+                const int rr = q + u * S + slot;
+                const int idx = __shfl(myidx, rr & 63);
                 ok[u] = active && rr < nrows;
                 v[u] = uintx4{0u, 0u, 0u, 0u};
                 if (ok[u]) v[u] = *(const uintx4*)(X + ((size_t)idx * d + col) * (16 / EPL));
@@ -111,28 +116,42 @@ __global__ __launch_bounds__(256) void segment_reduce_kernel(
 #pragma unroll
         for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], o);
     }
-    if (slot == 0 && active) {
-        float* out = partial + ((size_t)b * max_items + item) * d + col;
+    if (WPI == 1) {
+        if (slot == 0 && active) {
+            float* out = partial + ((size_t)b * max_items + item) * d + col;
 #pragma unroll
-        for (int e = 0; e < EPL; e += 4)
-            *(floatx4*)(out + e) = floatx4{acc[e], acc[e + 1], acc[e + 2], acc[e + 3]};
+            for (int e = 0; e < EPL; e += 4)
+                *(floatx4*)(out + e) = floatx4{acc[e], acc[e + 1], acc[e + 2], acc[e + 3]};
+        }
+        return;
+    }
+    if (slot == 0 && active) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) wsum[wave][col + e] = acc[e];
+    }
+    __syncthreads();
+    if (threadIdx.x < d) {
+        const int j = threadIdx.x;
+        const float s = ((wsum[0][j] + wsum[1][j]) + wsum[2][j]) + wsum[3][j];
+        partial[((size_t)b * max_items + item) * d + j] = s;
     }
 }
 
-// One workgroup of 256 threads per cluster: s_k = sum of the cluster's item rows in a fixed
+// One workgroup (256 threads, or 1024 when clusters have many items) per cluster: s_k = sum
+// of the cluster's item rows in a fixed
 // order, n_k = seg_off[k+1] - seg_off[k].  Optionally added onto sums/counts already stored
 // (chunked mode), optionally normalised into centroids (Algorithm 3, last loop; an empty
 // cluster keeps its previous centroid).  When c_frag is given, the rounded centroid is also
 // written in MFMA fragment order together with its score bias -||c||^2/2, so the next
 // assignment needs no separate re-layout pass.
-__global__ __launch_bounds__(256) void finalize_kernel(
+__global__ __launch_bounds__(1024) void finalize_kernel(
     const float* __restrict__ partial, const int32_t* __restrict__ seg_off,
     const int32_t* __restrict__ item_off, const float* C_prev, float* C_out,
     uint16_t* __restrict__ C_lp_out, float* __restrict__ C_lp_f32_out,
     uint16_t* __restrict__ c_frag, float* __restrict__ c_bias, int32_t* __restrict__ counts,
     float* __restrict__ sums, int d, int K, int64_t max_items, int ktiles, int dch,
     int accumulate, int normalise, int bf) {
-    __shared__ float red[1024];
+    __shared__ float red[4096];
     __shared__ float nrm[128];
     const int b = blockIdx.y, k = blockIdx.x, tid = threadIdx.x;
     seg_off += (size_t)b * (K + 1);
@@ -140,14 +159,26 @@ __global__ __launch_bounds__(256) void finalize_kernel(
     int dpow = 4;
     while (dpow < d) dpow <<= 1;
     const int LR = dpow >> 2;                     // threads per row, 4 features each
-    const int slots = 256 / LR, slot = tid / LR, col = (tid % LR) * 4;
+    const int slots = (int)blockDim.x / LR, slot = tid / LR, col = (tid % LR) * 4;
     const int i0 = item_off[k], i1 = item_off[k + 1];
     // read the running count before anyone overwrites it (barrier below)
     const int n_prev = accumulate ? counts[(size_t)b * K + k] : 0;
     const float* P = partial + (size_t)b * max_items * d;
+    // eight rows in flight per thread; the eight running sums are added in a fixed order
     floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-    if (col < d)
-        for (int it = i0 + slot; it < i1; it += slots) acc += *(const floatx4*)(P + (size_t)it * d + col);
+    if (col < d) {
+        floatx4 a8[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a8[u] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int it = i0 + slot; it < i1; it += 8 * slots) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int r = it + u * slots;
+                if (r < i1) a8[u] += *(const floatx4*)(P + (size_t)r * d + col);
+            }
+        }
+        acc = ((a8[0] + a8[1]) + (a8[2] + a8[3])) + ((a8[4] + a8[5]) + (a8[6] + a8[7]));
+    }
     *(floatx4*)&red[slot * dpow + col] = acc;
     __syncthreads();
     float c = 0.f;
@@ -205,19 +236,23 @@ fk_status launch_segment_reduce(const Geometry& g, const Workspace& w, const voi
                                 const int32_t* item_off, hipStream_t s) {
     const int epl = g.t == FK_F32 ? 4 : 8;
     const int lpr_log2 = ceil_log2((int)cdiv(g.d, epl));
-    dim3 grid((unsigned)cdiv(g.max_items, 4), g.B), block(256);
-    if (g.t == FK_F32)
-        hipLaunchKernelGGL((segment_reduce_kernel<4, false>), grid, block, 0, s, X, sorted_idx,
-                           seg_off, item_off, w.partial, g.N, g.d, g.K, g.rows_per_item,
-                           g.max_items, lpr_log2);
-    else if (g.t == FK_F16)
-        hipLaunchKernelGGL((segment_reduce_kernel<8, false>), grid, block, 0, s, X, sorted_idx,
-                           seg_off, item_off, w.partial, g.N, g.d, g.K, g.rows_per_item,
-                           g.max_items, lpr_log2);
-    else
-        hipLaunchKernelGGL((segment_reduce_kernel<8, true>), grid, block, 0, s, X, sorted_idx,
-                           seg_off, item_off, w.partial, g.N, g.d, g.K, g.rows_per_item,
-                           g.max_items, lpr_log2);
+    const bool wide = g.waves_per_item == 4;
+    dim3 grid((unsigned)(wide ? g.max_items : cdiv(g.max_items, 4)), g.B), block(256);
+#define FK_REDUCE(EPL, BF)                                                                        \
+    do {                                                                                          \
+        if (wide)                                                                                 \
+            hipLaunchKernelGGL((segment_reduce_kernel<EPL, BF, 4>), grid, block, 0, s, X,         \
+                               sorted_idx, seg_off, item_off, w.partial, g.N, g.d, g.K,           \
+                               g.rows_per_item, g.max_items, lpr_log2);                           \
+        else                                                                                      \
+            hipLaunchKernelGGL((segment_reduce_kernel<EPL, BF, 1>), grid, block, 0, s, X,         \
+                               sorted_idx, seg_off, item_off, w.partial, g.N, g.d, g.K,           \
+                               g.rows_per_item, g.max_items, lpr_log2);                           \
+    } while (0)
+    if (g.t == FK_F32) FK_REDUCE(4, false);
+    else if (g.t == FK_F16) FK_REDUCE(8, false);
+    else FK_REDUCE(8, true);
+#undef FK_REDUCE
     FK_HIP(hipGetLastError());
     return FK_OK;
 }
@@ -228,7 +263,9 @@ fk_status launch_finalize(const Geometry& g, const Workspace& w, const int32_t* 
     float* lp32 = g.t == FK_F32 ? (float*)a.C_out_lp : nullptr;
     if (lp32 == a.C_out_f32) lp32 = nullptr;
     uint16_t* frag = g.t == FK_F32 ? nullptr : (uint16_t*)a.c_frag;
-    hipLaunchKernelGGL(finalize_kernel, dim3(g.K, g.B), dim3(256), 0, s, w.partial, seg_off,
+    // few clusters with many partial rows each: more rows in flight per workgroup
+    const int threads = g.max_items / g.K > 64 ? 1024 : 256;
+    hipLaunchKernelGGL(finalize_kernel, dim3(g.K, g.B), dim3(threads), 0, s, w.partial, seg_off,
                        item_off, a.C_prev_f32, a.C_out_f32, lp16, lp32, frag, a.c_bias, a.counts,
                        a.sums, g.d, g.K, g.max_items, g.ktiles, g.dchunks, a.accumulate ? 1 : 0,
                        a.normalise ? 1 : 0, g.t == FK_BF16 ? 1 : 0);
