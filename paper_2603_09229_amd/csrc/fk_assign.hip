@@ -318,6 +318,165 @@ __global__ __launch_bounds__(WAVES * 64) void assign_mfma_kernel(
 }
 
 // ------------------------------------------------------------------------------------
+// Few centroids (all of C fits one LDS stage, K <= 32 * ST): the work per point is small and
+// the kernel is bound by streaming X from HBM.  Persistent waves: C is staged once per
+// workgroup, then every wave walks its own sequence of 32-point batches with no further
+// barrier.  A batch is copied global -> LDS (direct, no registers) with every load
+// instruction covering whole contiguous rows -- the MFMA operand pattern itself would touch
+// each 128-byte line four times with 32 bytes used per touch -- into one of two wave-private
+// LDS buffers, the next batch being requested before the current one is computed; the
+// fragments are then read back from LDS.  The 16-byte pieces of a row are stored XOR-swizzled
+// by the row number so that those reads are free of bank conflicts.  Same scores, packing and
+// tie rules as the sweeping kernel above.
+template <bool BF, int DCH, int WAVES, int KT>
+__global__ __launch_bounds__(WAVES * 64) void assign_mfma_stream_kernel(
+    const uint16_t* __restrict__ X, const uintx4* __restrict__ c_frag,
+    const float* __restrict__ c_bias, int32_t* __restrict__ assign,
+    float* __restrict__ min_dist, int64_t N, int d, int K, int ktiles) {
+    constexpr int kThreads = WAVES * 64;
+    constexpr int kRows = 32;                          // points per batch
+    // The centroid stage lives in its own LDS objects, the batch buffers in the dynamic one:
+    // the compiler can then tell that a copy in flight into a batch buffer does not alias the
+    // centroid reads, and does not make them wait for it.
+    __shared__ uintx4 sfrag[KT * DCH * 64];
+    __shared__ float sbias[KT * 32];
+    extern __shared__ uintx4 dyn_lds[];                // per wave: a ring of 3 batch buffers
+    const int ppr = d >> 3;                            // 16-byte pieces per row
+    const int slots = kRows * ppr;                     // pieces per batch
+    constexpr int loads = DCH;                         // load instructions per batch (some may be empty)
+    const int swz = (ppr & (ppr - 1)) == 0 ? min(ppr, 8) - 1 : 0;   // XOR mask for the piece index
+
+    const int b = blockIdx.y;
+    X += (size_t)b * N * d;
+    c_frag += (size_t)b * ktiles * DCH * 64;
+    c_bias += (size_t)b * ktiles * 32;
+    assign += (size_t)b * N;
+    if (min_dist) min_dist += (size_t)b * N;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, h = lane >> 5;
+    uintx4* ring = dyn_lds + (size_t)wave * 3 * loads * 64;
+
+    for (int o = tid; o < ktiles * DCH * 64; o += kThreads) sfrag[o] = c_frag[o];
+    for (int o = tid; o < ktiles * 32; o += kThreads) sbias[o] = c_bias[o];
+
+    const int64_t nbatches = (N + kRows - 1) / kRows;
+    const int64_t stride = (int64_t)gridDim.x * WAVES;
+    int64_t t = (int64_t)blockIdx.x * WAVES + wave;
+
+    // slot j of the buffer holds piece (j % ppr) ^ (row & swz) of row j / ppr
+    auto request = [&](int64_t batch, uintx4* buf) {
+        for (int q = 0; q < loads; ++q) {
+            const int j = q * 64 + lane;
+            const int row = j / ppr, piece = (j - row * ppr) ^ (row & swz);
+            const int64_t point = batch * kRows + row;
+            if (j < slots && point < N)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(X + (size_t)point * d + piece * 8),
+                    (__attribute__((address_space(3))) void*)(buf + q * 64), 16, 0, 0);
+        }
+    };
+
+    // Two batches are kept in flight.  Loads of a wave complete in order, so "at most `loads`
+    // outstanding" means that everything but the newest batch has landed.
+    if (t < nbatches) request(t, ring);
+    if (t + stride < nbatches) request(t + stride, ring + loads * 64);
+    if (t + stride < nbatches) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(loads) : "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();                       // C is in LDS; no workgroup barrier after this point
+
+    int cur = 0;
+    while (t < nbatches) {
+        const int64_t t1 = t + stride, t2 = t1 + stride;
+        const uintx4* bufc = ring + cur * (loads * 64);
+        uintx4* buf2 = ring + (cur == 0 ? 2 : cur - 1) * (loads * 64);   // read one iteration ago
+
+        // This lane's B operands: features [s*16 + h*8, +8) of point t*32 + n.  Read with an
+        // opaque LDS instruction: the wait for the copy that filled this buffer was issued by
+        // hand above / at the end of the previous iteration, and the compiler must not add a
+        // wait for the younger copy still in flight.
+        uintx4 xf[DCH];
+#pragma unroll
+        for (int s = 0; s < DCH; ++s) {
+            const int piece = 2 * s + h;
+            uintx4 v = {0u, 0u, 0u, 0u};
+            if (piece < ppr) {
+                const uint32_t addr = (uint32_t)(uintptr_t)(
+                    (__attribute__((address_space(3))) const void*)(bufc + n * ppr + (piece ^ (n & swz))));
+                asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(v) : "v"(addr) : "memory");
+            }
+            xf[s] = v;
+        }
+        const bool issued = t2 < nbatches;
+        if (issued) request(t2, buf2);
+
+        float best = -INFINITY;
+        int btile = 0;
+        for (int tt = 0; tt < ktiles; ++tt) {
+            floatx16 bias16;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const floatx4 bv = *(const floatx4*)&sbias[tt * 32 + 8 * q + 4 * h];
+                bias16[4 * q + 0] = bv[0];
+                bias16[4 * q + 1] = bv[1];
+                bias16[4 * q + 2] = bv[2];
+                bias16[4 * q + 3] = bv[3];
+            }
+            floatx16 acc = mfma32<BF>(sfrag[(tt * DCH) * 64 + lane], xf[0], bias16);
+#pragma unroll
+            for (int s = 1; s < DCH; ++s) acc = mfma32<BF>(sfrag[(tt * DCH + s) * 64 + lane], xf[s], acc);
+            const uint32_t bb = __float_as_uint(best);
+            const uint32_t fill = ~(uint32_t)((int32_t)bb >> 31) & 15u;
+            const float guard = __uint_as_float((bb & 0xFFFFFFF0u) | fill);
+            float m = guard;
+#pragma unroll
+            for (int i = 0; i < 16; i += 2) {
+                const float k0 = __uint_as_float((__float_as_uint(acc[i]) & 0xFFFFFFF0u) | (uint32_t)(15 - i));
+                const float k1 = __uint_as_float((__float_as_uint(acc[i + 1]) & 0xFFFFFFF0u) | (uint32_t)(14 - i));
+                m = __builtin_fmaxf(__builtin_fmaxf(m, k0), k1);
+            }
+            const bool improved = m != guard;
+            best = improved ? m : best;
+            btile = improved ? tt : btile;
+        }
+        {
+            const uint32_t bits = __float_as_uint(best);
+            const int i = 15 - (int)(bits & 15u);
+            int k = btile * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
+            float m = __uint_as_float(bits & 0xFFFFFFF0u);
+            const float om = __shfl_xor(m, 32);
+            const int ok = __shfl_xor(k, 32);
+            if (om > m || (om == m && ok < k)) { m = om; k = ok; }
+            k = min(k, K - 1);
+            const int64_t point = t * kRows + n;
+            float xnorm = 0.f;
+            if (min_dist) {
+#pragma unroll
+                for (int s = 0; s < DCH; ++s) {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const uint32_t w = xf[s][q];
+                        const float lo = lp_to_float((uint16_t)(w & 0xFFFFu), BF);
+                        const float hi = lp_to_float((uint16_t)(w >> 16), BF);
+                        xnorm += lo * lo + hi * hi;
+                    }
+                }
+                xnorm += __shfl_xor(xnorm, 32);
+            }
+            if (h == 0 && point < N) {
+                assign[point] = k;
+                if (min_dist) min_dist[point] = fmaxf(0.f, xnorm - 2.f * m);
+            }
+        }
+        // the next batch must have landed before it is read (wave-private buffers: no barrier)
+        if (issued) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(loads) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        t = t1;
+        cur = cur == 2 ? 0 : cur + 1;
+    }
+}
+
+// ------------------------------------------------------------------------------------
 // fp32: one point per thread, features in registers, centroid tiles of TK rows in LDS,
 // D_ik by direct differences in fp32; ascending k with strict '<'.
 template <int DMAX, int TK, int THREADS>
@@ -457,10 +616,55 @@ static int assign_variant() {
     return v;
 }
 
+// FK_ASSIGN_STREAM=0 keeps small-K shapes on the sweeping kernel (experiments).
+static bool stream_enabled() {
+    static bool on = [] {
+        const char* e = getenv("FK_ASSIGN_STREAM");
+        return !(e && atoi(e) == 0);
+    }();
+    return on;
+}
+
+static int device_cu_count() {
+    static int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 256;
+        return n > 0 ? n : 256;
+    }();
+    return cus;
+}
+
 template <bool BF, int DCH>
 static fk_status launch_mfma(const Geometry& g, const void* X, const void* frag,
                              const float* bias, int32_t* assign, float* min_dist,
                              hipStream_t s) {
+    constexpr int ST = (16 / DCH) < 8 ? (16 / DCH) : 8;
+    if (g.ktiles <= ST && stream_enabled()) {
+        // persistent waves: as many workgroups as fit the chip, each wave striding over
+        // 32-point batches
+        constexpr int WAVES = 4;
+        const size_t lds = (size_t)(WAVES * 3 * DCH * 64) * 16;
+        const bool one_tile = g.ktiles == 1;
+        auto kern = one_tile ? assign_mfma_stream_kernel<BF, DCH, WAVES, 1>
+                             : assign_mfma_stream_kernel<BF, DCH, WAVES, ST>;
+        static bool attr_set[2] = {false, false};
+        if (!attr_set[one_tile]) {
+            FK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+            attr_set[one_tile] = true;
+        }
+        int per_cu = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, WAVES * 64, lds) != hipSuccess || per_cu < 1)
+            per_cu = 1;
+        const int64_t nbatches = cdiv(g.N, 32);
+        int64_t wgs = (int64_t)device_cu_count() * per_cu;
+        if (wgs > cdiv(nbatches, WAVES)) wgs = cdiv(nbatches, WAVES);
+        dim3 grid((unsigned)wgs, g.B), block(WAVES * 64);
+        hipLaunchKernelGGL(kern, grid, block, lds, s, (const uint16_t*)X, (const uintx4*)frag, bias,
+                           assign, min_dist, g.N, g.d, g.K, g.ktiles);
+        FK_HIP(hipGetLastError());
+        return FK_OK;
+    }
     switch (assign_variant()) {
         case 1: return launch_mfma_v<BF, DCH, 4, 4>(g, X, frag, bias, assign, min_dist, s);
         case 0: return launch_mfma_v<BF, DCH, 2, 4>(g, X, frag, bias, assign, min_dist, s);

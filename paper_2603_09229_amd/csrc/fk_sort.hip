@@ -116,20 +116,12 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_hist_kernel(
         const int64_t nbase = base0 + (int64_t)(r + 1) * kSubTile;
         const bool more = r + 1 < rounds && nbase < N;
         if (more) load_round(keys, nbase, N, lane, kmax, kn);
-        if (NB <= 64) {
-            // hot bins would serialise per-key LDS atomics: one add per distinct digit and batch
+        // one LDS add per key: lanes that hit the same bin are serialised by the LDS unit, a
+        // few tens of cycles per instruction even for very hot bins, far cheaper than
+        // resolving the duplicates with ballots first
 #pragma unroll
-            for (int j = 0; j < kBatches; ++j) {
-                const bool valid = k[j] >= 0;
-                const int digit = valid ? (k[j] >> shift) & mask : 0;
-                const uint64_t peers = match_digit(digit, nbits, __ballot(valid));
-                if (valid && (peers & lanemask_lt()) == 0) atomicAdd(&hist[digit], __popcll(peers));
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < kBatches; ++j)
-                if (k[j] >= 0) atomicAdd(&hist[(k[j] >> shift) & mask], 1);
-        }
+        for (int j = 0; j < kBatches; ++j)
+            if (k[j] >= 0) atomicAdd(&hist[(k[j] >> shift) & mask], 1);
         if (!more) break;
 #pragma unroll
         for (int j = 0; j < kBatches; ++j) k[j] = kn[j];
