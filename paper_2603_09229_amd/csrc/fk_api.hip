@@ -232,7 +232,10 @@ int fk_stage_timer_stop(double* stage_ms, int* stage_launches) {
         stage_ms[st] += ms;
         stage_launches[st] += 1;
     }
-    return (int)g_timer.used;
+    const int n = (int)g_timer.used;
+    g_timer.used = 0;             // a later stop without a start reports nothing
+    g_timer.stage.clear();
+    return n;
 }
 
 size_t fk_workspace_bytes(int B, int64_t N, int d, int K, fk_dtype t) {

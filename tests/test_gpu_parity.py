@@ -254,3 +254,33 @@ def test_bad_arguments_are_errors_not_crashes():
     assert e.value.status == 2          # d not a multiple of 8
     with pytest.raises(ValueError):
         fk.fk_lloyd_ooc(torch.zeros((64, 16), dtype=torch.float16), C[0].float(), 1, dev_ws=small)
+
+
+def test_stage_timer_reports_every_stage():
+    w = wl.C2.scaled(N=30000, K=128)
+    X = wl.make_points(w).to(DEV)
+    C = wl.gather_rows(X.cpu(), wl.init_rows(w)).to(DEV)
+    fk.fk_stage_timer_start()
+    fk.fk_lloyd_iter(X, C, 3)
+    st = fk.fk_stage_timer_stop()
+    assert set(st) == {"assign", "sort", "reduce", "finalize"}
+    for name, (ms, n) in st.items():
+        assert n == 3 and ms > 0.0, (name, ms, n)
+    # stopped: further calls record nothing
+    fk.fk_lloyd_iter(X, C, 1)
+    assert all(v == (0.0, 0) for v in fk.fk_stage_timer_stop().values())
+
+
+def test_results_do_not_depend_on_the_stream():
+    w = wl.C2.scaled(N=20000, K=96)
+    X = wl.make_points(w).to(DEV)
+    C0 = wl.gather_rows(X.cpu(), wl.init_rows(w)).to(DEV)
+    Ca, Cb = C0.clone(), C0.clone()
+    a1, n1, _ = fk.fk_lloyd_iter(X, Ca, 2)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        a2, n2, _ = fk.fk_lloyd_iter(X, Cb, 2)
+    side.synchronize()
+    torch.cuda.synchronize()
+    assert torch.equal(Ca, Cb) and torch.equal(a1, a2) and torch.equal(n1, n2)
