@@ -141,6 +141,7 @@ def main() -> int:
                 "frac": t / PEAK_FP32_VALU_TFLOPS, "traffic": None,
                 "avg_launch_ms": avg["assign"]}
     else:
+        # few centroids: both big kernels stream X; the row gather of the update is reported
         red_bytes = w.B * (w.N * (w.d * es + 4))
         g = red_bytes / (avg["reduce"] * 1e-3) / 1e9
         roof = {"kernel": "segment_reduce_kernel", "bound": "hbm", "achieved": g,
