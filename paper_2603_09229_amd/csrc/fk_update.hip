@@ -264,7 +264,10 @@ fk_status launch_finalize(const Geometry& g, const Workspace& w, const int32_t* 
     if (lp32 == a.C_out_f32) lp32 = nullptr;
     uint16_t* frag = g.t == FK_F32 ? nullptr : (uint16_t*)a.c_frag;
     // few clusters with many partial rows each: more rows in flight per workgroup
-    const int threads = g.max_items / g.K > 64 ? 1024 : 256;
+    // ... and many clusters with one or two rows each: the smallest workgroup that still has a
+    // thread per feature
+    int threads = g.max_items / g.K > 64 ? 1024 : 256;
+    if (g.max_items / g.K <= 4) threads = g.d <= 64 ? 64 : 128;
     hipLaunchKernelGGL(finalize_kernel, dim3(g.K, g.B), dim3(threads), 0, s, w.partial, seg_off,
                        item_off, a.C_prev_f32, a.C_out_f32, lp16, lp32, frag, a.c_bias, a.counts,
                        a.sums, g.d, g.K, g.max_items, g.ktiles, g.dchunks, a.accumulate ? 1 : 0,
