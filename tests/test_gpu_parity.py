@@ -284,3 +284,32 @@ def test_results_do_not_depend_on_the_stream():
     side.synchronize()
     torch.cuda.synchronize()
     assert torch.equal(Ca, Cb) and torch.equal(a1, a2) and torch.equal(n1, n2)
+
+
+def test_random_shapes_full_iteration():
+    """Seeded sweep over odd shapes: every dtype, ragged N, K on both sides of the tile and
+    stage boundaries, d every multiple of 8; one full iteration each against the oracle."""
+    rng = np.random.default_rng(2024)
+    dts = [torch.float16, torch.bfloat16, torch.float32]
+    for case in range(40):
+        dtype = dts[case % 3]
+        d = int(rng.integers(1, 17)) * 8
+        K = int(rng.choice([1, 2, 3, 17, 31, 32, 33, 63, 64, 65, 100, 127, 128, 129, 255, 257, 513,
+                            1000, 2047, 2048, 2049, 3000]))
+        N = int(rng.integers(1, 6000))
+        B = int(rng.choice([1, 1, 2, 3]))
+        w = wl.Workload("r", B, N, d, K, {torch.float16: "fp16", torch.bfloat16: "bf16",
+                                          torch.float32: "fp32"}[dtype], 3.0, 1.0, 0.0, 1, 5000 + case)
+        X = wl.make_points(w)
+        idx = torch.randint(0, N, (B, K), generator=torch.Generator().manual_seed(case))
+        C0 = wl.gather_rows(X, idx)
+        C = C0.to(DEV).clone()
+        a, counts, C_lp = fk.fk_lloyd_iter(X.to(DEV), C, 1)
+        torch.cuda.synchronize()
+        consumed = C0.to(dtype)
+        for b in range(B):
+            Xb = parity.widen(X[b])
+            parity.check_assign(Xb, parity.widen(consumed[b]), a[b].cpu().numpy())
+            parity.check_update(Xb, a[b].cpu().numpy(), C0[b].numpy(), C[b].cpu().numpy(),
+                                counts[b].cpu().numpy(), parity.CENTROID_TOL[dtype])
+        assert torch.equal(C_lp.cpu(), C.cpu().to(dtype)), (case, dtype, B, N, d, K)
