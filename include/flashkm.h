@@ -26,7 +26,7 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work on it and return without waiting, except fk_lloyd_ooc.
  *   - Supported shapes: 1 <= K <= 65536, 1 <= N, B*N < 2^31, B >= 1,
- *     d a multiple of 8 with 8 <= d <= 128.  Anything else returns FK_EUNSUPPORTED or
+ *     d a multiple of 8 with 8 <= d <= 512.  Anything else returns FK_EUNSUPPORTED or
  *     FK_EINVAL; there is no fallback path.
  *   - Every function returns an fk_status; on failure fk_last_error() holds a message for
  *     the calling thread.  Nothing throws or aborts.

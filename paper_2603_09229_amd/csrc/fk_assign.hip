@@ -12,6 +12,8 @@
 // fp32 inputs: plain fp32 direct differences, one point per thread, centroid tiles in LDS.
 #include <stdlib.h>
 
+#include <algorithm>
+
 #include "fk_common.h"
 
 namespace fk {
@@ -51,12 +53,11 @@ template <bool SRC_F32>
 __global__ __launch_bounds__(512) void centroid_layout_kernel(
     const void* __restrict__ src, uint16_t* __restrict__ C_lp, uint16_t* __restrict__ c_frag,
     float* __restrict__ c_bias, int d, int K, int ktiles, int dch, int bf) {
-    __shared__ float part[32][17];
+    __shared__ float part[32][65];
     const int b = blockIdx.y, kt = blockIdx.x;
-    const int g = threadIdx.x;
-    const int l = g & 63, s = g >> 6, r = l & 31, h = l >> 5;
-    const int k = kt * 32 + r, j0 = s * 16 + h * 8;
-    if (s < dch) {
+    for (int g = threadIdx.x; g < 64 * dch; g += blockDim.x) {
+        const int l = g & 63, s = g >> 6, r = l & 31, h = l >> 5;
+        const int k = kt * 32 + r, j0 = s * 16 + h * 8;
         uint16_t v[8];
         float ss = 0.f;
         const bool live = (k < K) && (j0 < d);
@@ -89,9 +90,10 @@ __global__ __launch_bounds__(512) void centroid_layout_kernel(
         part[r][s * 2 + h] = ss;
     }
     __syncthreads();
-    if (g < 32) {
+    if (threadIdx.x < 32) {
+        const int g = threadIdx.x;
         float n2 = 0.f;
-        for (int q = 0; q < dch * 2; ++q) n2 += part[g][q];   // fixed order
+        for (int q = 0; q < dch * 2; ++q) n2 = __fadd_rn(n2, part[g][q]);   // fixed order
         const int kk = kt * 32 + g;
         c_bias[((size_t)b * ktiles + kt) * 32 + g] = kk < K ? -0.5f * n2 : kPadBias;
     }
@@ -99,7 +101,7 @@ __global__ __launch_bounds__(512) void centroid_layout_kernel(
 
 fk_status launch_prepare_centroids(const Geometry& g, const void* C_lp, void* c_frag,
                                    float* c_bias, hipStream_t s) {
-    dim3 grid(g.ktiles, g.B), block(64 * g.dchunks);
+    dim3 grid(g.ktiles, g.B), block(std::min(512, 64 * g.dchunks));
     hipLaunchKernelGGL(centroid_layout_kernel<false>, grid, block, 0, s, C_lp, (uint16_t*)nullptr,
                        (uint16_t*)c_frag, c_bias, g.d, g.K, g.ktiles, g.dchunks,
                        g.t == FK_BF16 ? 1 : 0);
@@ -123,7 +125,7 @@ fk_status launch_round_centroids(const Geometry& g, const float* C_f32, void* C_
         }
         return FK_OK;
     }
-    dim3 grid(g.ktiles, g.B), block(64 * g.dchunks);
+    dim3 grid(g.ktiles, g.B), block(std::min(512, 64 * g.dchunks));
     hipLaunchKernelGGL(centroid_layout_kernel<true>, grid, block, 0, s, (const void*)C_f32,
                        (uint16_t*)C_lp, (uint16_t*)c_frag, c_bias, g.d, g.K, g.ktiles, g.dchunks,
                        g.t == FK_BF16 ? 1 : 0);
@@ -314,6 +316,133 @@ __global__ __launch_bounds__(WAVES * 64) void assign_mfma_kernel(
             assign[point] = k;
             if (min_dist) min_dist[point] = fmaxf(0.f, xn - 2.f * m);
         }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Wide features (128 < d <= 512; DCH = 16 or 32 chunks of 16).  Same sweep as above with one
+// 32-point tile per wave, so that a point's features still fit the register file (4*DCH
+// VGPRs), and LDS stages of 16 chunks: a whole centroid tile per stage for DCH = 16, half a
+// tile for DCH = 32 (the MFMA chain of a tile then runs across two stages).
+template <bool BF, int DCH, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void assign_mfma_wide_kernel(
+    const uint16_t* __restrict__ X, const uintx4* __restrict__ c_frag,
+    const float* __restrict__ c_bias, int32_t* __restrict__ assign,
+    float* __restrict__ min_dist, int64_t N, int d, int K, int ktiles) {
+    constexpr int SC = 16;                  // chunks (1 KiB pieces) per stage
+    constexpr int SPT = DCH / SC;           // stages per centroid tile
+    constexpr int kThreads = WAVES * 64;
+    static_assert(DCH % SC == 0 && SC % WAVES == 0 && kThreads >= 32, "stage geometry");
+    __shared__ uintx4 sfrag[2][SC * 64];
+    __shared__ float sbias[2][32];
+
+    const int b = blockIdx.y;
+    X += (size_t)b * N * d;
+    c_frag += (size_t)b * ktiles * DCH * 64;
+    c_bias += (size_t)b * ktiles * 32;
+    assign += (size_t)b * N;
+    if (min_dist) min_dist += (size_t)b * N;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 31, h = lane >> 5;
+    const int64_t point = ((int64_t)blockIdx.x * WAVES + wave) * 32 + n;
+    const int nst = ktiles * SPT;
+
+    auto fetch = [&](int st, int buf) -> float {
+#pragma unroll
+        for (int q = 0; q < SC / WAVES; ++q) {
+            const int pc = q * WAVES + wave;                       // wave-uniform
+            copy16_to_lds(c_frag + ((size_t)(st * SC + pc) * 64 + lane), &sfrag[buf][pc * 64]);
+        }
+        float bv = kPadBias;
+        if (tid < 32) bv = c_bias[(st / SPT) * 32 + tid];
+        return bv;
+    };
+
+    float pre_bias = fetch(0, 0);
+    uintx4 xf[DCH];
+#pragma unroll
+    for (int s = 0; s < DCH; ++s) {
+        const int j0 = s * 16 + h * 8;
+        uintx4 v = {0u, 0u, 0u, 0u};
+        if (point < N && j0 < d) v = *(const uintx4*)(X + (size_t)point * d + j0);
+        xf[s] = v;
+    }
+    float best = -INFINITY;
+    int btile = 0;
+    if (tid < 32) sbias[0][tid] = pre_bias;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    floatx16 acc;
+    for (int st0 = 0; st0 < nst; st0 += SPT) {
+#pragma unroll
+        for (int half = 0; half < SPT; ++half) {
+            const int st = st0 + half;
+            const int buf = st & 1;
+            if (st + 1 < nst) pre_bias = fetch(st + 1, buf ^ 1);   // lands during the sweep
+            if (half == 0) {
+                // accumulator slot i is centroid row 8*(i/4) + 4*h + i%4 of this tile
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const floatx4 bv = *(const floatx4*)&sbias[buf][8 * q + 4 * h];
+                    acc[4 * q + 0] = bv[0];
+                    acc[4 * q + 1] = bv[1];
+                    acc[4 * q + 2] = bv[2];
+                    acc[4 * q + 3] = bv[3];
+                }
+            }
+#pragma unroll
+            for (int s = 0; s < SC; ++s)
+                acc = mfma32<BF>(sfrag[buf][s * 64 + lane], xf[half * SC + s], acc);
+            if (half == SPT - 1) {
+                const uint32_t bb = __float_as_uint(best);
+                const uint32_t fill = ~(uint32_t)((int32_t)bb >> 31) & 15u;
+                const float guard = __uint_as_float((bb & 0xFFFFFFF0u) | fill);
+                float m = guard;
+#pragma unroll
+                for (int i = 0; i < 16; i += 2) {
+                    const float k0 = __uint_as_float((__float_as_uint(acc[i]) & 0xFFFFFFF0u) | (uint32_t)(15 - i));
+                    const float k1 = __uint_as_float((__float_as_uint(acc[i + 1]) & 0xFFFFFFF0u) | (uint32_t)(14 - i));
+                    m = __builtin_fmaxf(__builtin_fmaxf(m, k0), k1);
+                }
+                const bool improved = m != guard;
+                best = improved ? m : best;
+                btile = improved ? st / SPT : btile;
+            }
+            if (st + 1 < nst) {
+                if (tid < 32) sbias[buf ^ 1][tid] = pre_bias;
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+            __syncthreads();
+        }
+    }
+
+    const uint32_t bits = __float_as_uint(best);
+    const int i = 15 - (int)(bits & 15u);
+    int k = btile * 32 + 8 * (i >> 2) + 4 * h + (i & 3);
+    float m = __uint_as_float(bits & 0xFFFFFFF0u);
+    const float om = __shfl_xor(m, 32);
+    const int ok = __shfl_xor(k, 32);
+    if (om > m || (om == m && ok < k)) { m = om; k = ok; }
+    k = min(k, K - 1);
+    float xnorm = 0.f;
+    if (min_dist) {
+#pragma unroll
+        for (int s = 0; s < DCH; ++s) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t w = xf[s][q];
+                const float lo = lp_to_float((uint16_t)(w & 0xFFFFu), BF);
+                const float hi = lp_to_float((uint16_t)(w >> 16), BF);
+                xnorm += lo * lo + hi * hi;
+            }
+        }
+        xnorm += __shfl_xor(xnorm, 32);
+    }
+    if (h == 0 && point < N) {
+        assign[point] = k;
+        if (min_dist) min_dist[point] = fmaxf(0.f, xnorm - 2.f * m);
     }
 }
 
@@ -525,6 +654,59 @@ __global__ __launch_bounds__(THREADS) void assign_f32_kernel(
     }
 }
 
+// fp32 with wide features (128 < d <= 512): the point no longer fits in registers, so each
+// thread keeps 16 running distances (one per row of the LDS centroid tile) and walks its own
+// row of X in blocks of 32 features, once per centroid tile (the re-reads come from cache).
+__global__ __launch_bounds__(256) void assign_f32_wide_kernel(
+    const float* __restrict__ X, const float* __restrict__ C, int32_t* __restrict__ assign,
+    float* __restrict__ min_dist, int64_t N, int d, int K) {
+    constexpr int TK = 16;
+    extern __shared__ float sc_dyn[];                  // [TK][d]
+    const int b = blockIdx.y;
+    X += (size_t)b * N * d;
+    C += (size_t)b * K * d;
+    assign += (size_t)b * N;
+    if (min_dist) min_dist += (size_t)b * N;
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const float* xrow = X + (size_t)(i < N ? i : 0) * d;
+    float m = INFINITY;
+    int a = 0;
+    for (int k0 = 0; k0 < K; k0 += TK) {
+        __syncthreads();
+        for (int o = threadIdx.x; o < TK * d; o += 256) {
+            const int r = o / d, j = o - r * d;
+            sc_dyn[o] = k0 + r < K ? C[(size_t)(k0 + r) * d + j] : 0.f;
+        }
+        __syncthreads();
+        float D[TK];
+#pragma unroll
+        for (int r = 0; r < TK; ++r) D[r] = 0.f;
+        for (int j0 = 0; j0 < d; j0 += 8) {             // d is a multiple of 8
+            const floatx4 xa = *(const floatx4*)(xrow + j0);
+            const floatx4 xb = *(const floatx4*)(xrow + j0 + 4);
+#pragma unroll
+            for (int r = 0; r < TK; ++r) {
+                const floatx4 ca = *(const floatx4*)&sc_dyn[r * d + j0];
+                const floatx4 cb = *(const floatx4*)&sc_dyn[r * d + j0 + 4];
+                const float e0 = xa[0] - ca[0], e1 = xa[1] - ca[1], e2 = xa[2] - ca[2], e3 = xa[3] - ca[3];
+                const float e4 = xb[0] - cb[0], e5 = xb[1] - cb[1], e6 = xb[2] - cb[2], e7 = xb[3] - cb[3];
+                float t = D[r];
+                t += e0 * e0; t += e1 * e1; t += e2 * e2; t += e3 * e3;
+                t += e4 * e4; t += e5 * e5; t += e6 * e6; t += e7 * e7;
+                D[r] = t;
+            }
+        }
+        const int nk = min(TK, K - k0);
+#pragma unroll
+        for (int r = 0; r < TK; ++r)
+            if (r < nk && D[r] < m) { m = D[r]; a = k0 + r; }
+    }
+    if (i < N) {
+        assign[i] = a;
+        if (min_dist) min_dist[i] = m;
+    }
+}
+
 // Small fp32 problems: 64 points per workgroup, the four waves split every 32-row centroid
 // tile between them (8 rows each), then the four candidates of a point are merged through
 // LDS (smaller distance first, lower index on equal distances).  Four times the parallelism
@@ -673,6 +855,19 @@ static fk_status launch_mfma(const Geometry& g, const void* X, const void* frag,
     }
 }
 
+template <bool BF, int DCH>
+static fk_status launch_mfma_wide(const Geometry& g, const void* X, const void* frag,
+                                  const float* bias, int32_t* assign, float* min_dist,
+                                  hipStream_t s) {
+    constexpr int WAVES = 8;
+    dim3 grid((unsigned)cdiv(g.N, WAVES * 32), g.B), block(WAVES * 64);
+    hipLaunchKernelGGL((assign_mfma_wide_kernel<BF, DCH, WAVES>), grid, block, 0, s,
+                       (const uint16_t*)X, (const uintx4*)frag, bias, assign, min_dist, g.N, g.d,
+                       g.K, g.ktiles);
+    FK_HIP(hipGetLastError());
+    return FK_OK;
+}
+
 template <bool BF>
 static fk_status launch_mfma_d(const Geometry& g, const void* X, const void* frag,
                                const float* bias, int32_t* assign, float* min_dist,
@@ -681,6 +876,8 @@ static fk_status launch_mfma_d(const Geometry& g, const void* X, const void* fra
         case 2: return launch_mfma<BF, 2>(g, X, frag, bias, assign, min_dist, s);
         case 4: return launch_mfma<BF, 4>(g, X, frag, bias, assign, min_dist, s);
         case 8: return launch_mfma<BF, 8>(g, X, frag, bias, assign, min_dist, s);
+        case 16: return launch_mfma_wide<BF, 16>(g, X, frag, bias, assign, min_dist, s);
+        case 32: return launch_mfma_wide<BF, 32>(g, X, frag, bias, assign, min_dist, s);
     }
     set_error("assign: no kernel for %d feature chunks", g.dchunks);
     return FK_EUNSUPPORTED;
@@ -690,10 +887,16 @@ fk_status launch_assign(const Geometry& g, const void* X, const void* C_or_frag,
                         const float* c_bias, int32_t* assign, float* min_dist, hipStream_t s) {
     if (g.t == FK_F16) return launch_mfma_d<false>(g, X, C_or_frag, c_bias, assign, min_dist, s);
     if (g.t == FK_BF16) return launch_mfma_d<true>(g, X, C_or_frag, c_bias, assign, min_dist, s);
-    // small problems: split each centroid tile over the waves, so that even 16K points spread
-    // over the chip
     const float* Xf = (const float*)X;
     const float* Cf = (const float*)C_or_frag;
+    if (g.d > 128) {
+        hipLaunchKernelGGL(assign_f32_wide_kernel, dim3((unsigned)cdiv(g.N, 256), g.B), dim3(256),
+                           (size_t)16 * g.d * sizeof(float), s, Xf, Cf, assign, min_dist, g.N, g.d, g.K);
+        FK_HIP(hipGetLastError());
+        return FK_OK;
+    }
+    // small problems: split each centroid tile over the waves, so that even 16K points spread
+    // over the chip
     const bool small = (int64_t)g.B * g.N < ((int64_t)1 << 18);
     dim3 grid((unsigned)cdiv(g.N, small ? 64 : 256), g.B), block(256);
 #define FK_F32_LAUNCH(DM)                                                                         \

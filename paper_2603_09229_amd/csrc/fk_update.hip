@@ -59,7 +59,7 @@ __global__ __launch_bounds__(256) void segment_reduce_kernel(
     const int32_t* __restrict__ seg_off, const int32_t* __restrict__ item_off,
     float* __restrict__ partial, int64_t N, int d, int K, int R, int64_t max_items,
     int lpr_log2) {
-    __shared__ float wsum[4][128];
+    __shared__ float wsum[WPI == 4 ? 4 : 1][WPI == 4 ? 512 : 1];
     const int b = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t item = WPI == 4 ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave;
@@ -74,66 +74,70 @@ __global__ __launch_bounds__(256) void segment_reduce_kernel(
     const int end = min(seg_off[k + 1], start + R);
 
     const int LPR = 1 << lpr_log2, S = 64 >> lpr_log2;
-    const int slot = lane >> lpr_log2, col = (lane & (LPR - 1)) * EPL;
-    const bool active = col < d;
+    const int slot = lane >> lpr_log2;
     const char* X = (const char*)Xv + (size_t)b * N * d * (16 / EPL);
-    float acc[EPL];
+    // rows wider than one wave-load (64 lanes x 16 bytes) are reduced one column block at a time
+    const int ncb = (d + 64 * EPL - 1) / (64 * EPL);
+    for (int cb = 0; cb < ncb; ++cb) {
+        const int col = cb * 64 * EPL + (lane & (LPR - 1)) * EPL;
+        const bool active = col < d;
+        float acc[EPL];
 #pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+        for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
 
-    constexpr int U = 8;
-    for (int r0 = start + part * 64; r0 < end; r0 += 64 * WPI) {
-        const int nrows = min(64, end - r0);
-        const int myidx = lane < nrows ? sorted_idx[r0 + lane] : 0;
-        for (int q = 0; q < nrows; q += S * U) {
-            uintx4 v[U];
-            bool ok[U];
+        constexpr int U = 8;
+        for (int r0 = start + part * 64; r0 < end; r0 += 64 * WPI) {
+            const int nrows = min(64, end - r0);
+            const int myidx = lane < nrows ? sorted_idx[r0 + lane] : 0;
+            for (int q = 0; q < nrows; q += S * U) {
+                uintx4 v[U];
+                bool ok[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int rr = q + u * S + slot;
-                const int idx = __shfl(myidx, rr & 63);
-                ok[u] = active && rr < nrows;
-                v[u] = uintx4{0u, 0u, 0u, 0u};
-                if (ok[u]) v[u] = *(const uintx4*)(X + ((size_t)idx * d + col) * (16 / EPL));
-            }
+                for (int u = 0; u < U; ++u) {
+                    const int rr = q + u * S + slot;
+                    const int idx = __shfl(myidx, rr & 63);
+                    ok[u] = active && rr < nrows;
+                    v[u] = uintx4{0u, 0u, 0u, 0u};
+                    if (ok[u]) v[u] = *(const uintx4*)(X + ((size_t)idx * d + col) * (16 / EPL));
+                }
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (EPL == 4) {
+                for (int u = 0; u < U; ++u) {
+                    if (EPL == 4) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[e] += __uint_as_float(v[u][e]);
-                } else {
+                        for (int e = 0; e < 4; ++e) acc[e] += __uint_as_float(v[u][e]);
+                    } else {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        acc[2 * e] += lp_to_float((uint16_t)(v[u][e] & 0xFFFFu), BF);
-                        acc[2 * e + 1] += lp_to_float((uint16_t)(v[u][e] >> 16), BF);
+                        for (int e = 0; e < 4; ++e) {
+                            acc[2 * e] += lp_to_float((uint16_t)(v[u][e] & 0xFFFFu), BF);
+                            acc[2 * e + 1] += lp_to_float((uint16_t)(v[u][e] >> 16), BF);
+                        }
                     }
                 }
             }
         }
-    }
-    // add the row slots of the wave together (fixed butterfly order)
-    for (int o = LPR; o < 64; o <<= 1) {
+        // add the row slots of the wave together (fixed butterfly order)
+        for (int o = LPR; o < 64; o <<= 1) {
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], o);
-    }
-    if (WPI == 1) {
-        if (slot == 0 && active) {
-            float* out = partial + ((size_t)b * max_items + item) * d + col;
-#pragma unroll
-            for (int e = 0; e < EPL; e += 4)
-                *(floatx4*)(out + e) = floatx4{acc[e], acc[e + 1], acc[e + 2], acc[e + 3]};
+            for (int e = 0; e < EPL; ++e) acc[e] += __shfl_xor(acc[e], o);
         }
-        return;
-    }
-    if (slot == 0 && active) {
+        if (slot == 0 && active) {
+            if (WPI == 1) {
+                float* out = partial + ((size_t)b * max_items + item) * d + col;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) wsum[wave][col + e] = acc[e];
+                for (int e = 0; e < EPL; e += 4)
+                    *(floatx4*)(out + e) = floatx4{acc[e], acc[e + 1], acc[e + 2], acc[e + 3]};
+            } else {
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) wsum[wave][col + e] = acc[e];
+            }
+        }
     }
-    __syncthreads();
-    if (threadIdx.x < d) {
-        const int j = threadIdx.x;
-        const float s = ((wsum[0][j] + wsum[1][j]) + wsum[2][j]) + wsum[3][j];
-        partial[((size_t)b * max_items + item) * d + j] = s;
+    if (WPI == 4) {
+        __syncthreads();
+        for (int j = threadIdx.x; j < d; j += 256) {
+            const float s = ((wsum[0][j] + wsum[1][j]) + wsum[2][j]) + wsum[3][j];
+            partial[((size_t)b * max_items + item) * d + j] = s;
+        }
     }
 }
 
@@ -152,7 +156,7 @@ __global__ __launch_bounds__(1024) void finalize_kernel(
     float* __restrict__ sums, int d, int K, int64_t max_items, int ktiles, int dch,
     int accumulate, int normalise, int bf) {
     __shared__ float red[4096];
-    __shared__ float nrm[128];
+    __shared__ float nrm[512];
     const int b = blockIdx.y, k = blockIdx.x, tid = threadIdx.x;
     seg_off += (size_t)b * (K + 1);
     item_off += (size_t)b * (K + 1);
@@ -181,35 +185,32 @@ __global__ __launch_bounds__(1024) void finalize_kernel(
     }
     *(floatx4*)&red[slot * dpow + col] = acc;
     __syncthreads();
-    float c = 0.f;
-    uint16_t lp = 0;
-    int n = 0;
-    if (tid < d) {
+    const int T = (int)blockDim.x;
+    const int n = seg_off[k + 1] - seg_off[k] + n_prev;
+    for (int j = tid; j < d; j += T) {
         float s = 0.f;
-        for (int q = 0; q < slots; ++q) s += red[q * dpow + tid];   // fixed order
-        const size_t o = ((size_t)b * K + k) * d + tid;
-        n = seg_off[k + 1] - seg_off[k] + n_prev;
+        for (int q = 0; q < slots; ++q) s += red[q * dpow + j];   // fixed order
+        const size_t o = ((size_t)b * K + k) * d + j;
         if (accumulate) s += sums[o];
         if (sums) sums[o] = s;
         if (normalise) {
-            c = n > 0 ? (float)((double)s / (double)n) : C_prev[o];
+            const float c = n > 0 ? (float)((double)s / (double)n) : C_prev[o];
             C_out[o] = c;
-            lp = float_to_lp(c, bf);
+            const uint16_t lp = float_to_lp(c, bf);
             if (C_lp_out) C_lp_out[o] = lp;
             if (C_lp_f32_out) C_lp_f32_out[o] = c;
+            if (c_frag) {
+                // fragment order: tile k/32, chunk j/16, lane (j%16)/8*32 + k%32, element j%8
+                const size_t pos = ((((size_t)b * ktiles + (k >> 5)) * dch + (j >> 4)) * 64 +
+                                    (((j >> 3) & 1) << 5) + (k & 31)) * 8 + (j & 7);
+                c_frag[pos] = lp;
+                const float f = lp_to_float(lp, bf);
+                nrm[j] = __fmul_rn(f, f);
+            }
         }
-        if (tid == 0) counts[(size_t)b * K + k] = n;
     }
+    if (tid == 0) counts[(size_t)b * K + k] = n;
     if (normalise && c_frag) {
-        // fragment order: tile k/32, chunk j/16, lane (j%16)/8*32 + k%32, element j%8
-        if (tid < d) {
-            const int j = tid;
-            const size_t pos = ((((size_t)b * ktiles + (k >> 5)) * dch + (j >> 4)) * 64 +
-                                (((j >> 3) & 1) << 5) + (k & 31)) * 8 + (j & 7);
-            c_frag[pos] = lp;
-            const float f = lp_to_float(lp, bf);
-            nrm[tid] = __fmul_rn(f, f);
-        }
         __syncthreads();
         if (tid == 0) {
             // same association as the stand-alone layout kernel: groups of 8 features first
@@ -235,7 +236,8 @@ fk_status launch_segment_reduce(const Geometry& g, const Workspace& w, const voi
                                 const int32_t* sorted_idx, const int32_t* seg_off,
                                 const int32_t* item_off, hipStream_t s) {
     const int epl = g.t == FK_F32 ? 4 : 8;
-    const int lpr_log2 = ceil_log2((int)cdiv(g.d, epl));
+    int lpr_log2 = ceil_log2((int)cdiv(g.d, epl));
+    if (lpr_log2 > 6) lpr_log2 = 6;          // wider rows go column block by column block
     const bool wide = g.waves_per_item == 4;
     dim3 grid((unsigned)(wide ? g.max_items : cdiv(g.max_items, 4)), g.B), block(256);
 #define FK_REDUCE(EPL, BF)                                                                        \
@@ -267,7 +269,7 @@ fk_status launch_finalize(const Geometry& g, const Workspace& w, const int32_t* 
     // ... and many clusters with one or two rows each: the smallest workgroup that still has a
     // thread per feature
     int threads = g.max_items / g.K > 64 ? 1024 : 256;
-    if (g.max_items / g.K <= 4) threads = g.d <= 64 ? 64 : 128;
+    if (g.max_items / g.K <= 4 && g.d <= 128) threads = g.d <= 64 ? 64 : 128;
     hipLaunchKernelGGL(finalize_kernel, dim3(g.K, g.B), dim3(threads), 0, s, w.partial, seg_off,
                        item_off, a.C_prev_f32, a.C_out_f32, lp16, lp32, frag, a.c_bias, a.counts,
                        a.sums, g.d, g.K, g.max_items, g.ktiles, g.dchunks, a.accumulate ? 1 : 0,

@@ -49,7 +49,11 @@ C2 = Workload("c2_mid_fp16", 1, 1 << 20, 128, 1024, "fp16", 4.0, 1.0, 0.0, 20, 1
 C3 = Workload("c3_batched_bf16", 32, 32768, 128, 256, "bf16", 1.0, 0.5, 0.0, 10, 1003)
 C4 = Workload("c4_skewed_fp16", 1, 1 << 24, 64, 16, "fp16", 8.0, 1.0, 1.2, 20, 1004)
 C5 = Workload("c5_ooc_fp16", 1, 1 << 28, 128, 65536, "fp16", 4.0, 1.0, 0.0, 5, 1005)
-CONFIGS = {w.name: w for w in (C1, C2, C3, C4, C5)}
+# A shape the paper quotes for its large-N / large-K regime (Section 5.2: N = 1M, K = 64K,
+# D = 512); not one of the five benchmark configurations, used to exercise the wide-feature
+# kernels at scale.
+P512 = Workload("paper_large_k_d512_fp16", 1, 1 << 20, 512, 65536, "fp16", 4.0, 1.0, 0.0, 3, 1006)
+CONFIGS = {w.name: w for w in (C1, C2, C3, C4, C5, P512)}
 
 
 def _gen(seed: int, device) -> torch.Generator:

@@ -88,6 +88,12 @@ def test_c4_full_size_skewed():
     _run_incore(wl.C4, n_points=8192, n_clusters=4, instances=[0])
 
 
+def test_paper_large_k_d512_shape():
+    """N = 2^20, K = 65536, d = 512 (a shape the paper quotes for its large-N / large-K
+    regime): wide-feature kernels and the two-pass sort at scale, sampled against the oracle."""
+    _run_incore(wl.P512, n_points=512, n_clusters=32, instances=[0], iters=1)
+
+
 def test_c5_recipe_out_of_core_large_k():
     """The out-of-core configuration's recipe (K = 65536, d = 128, fp16, X in pinned host
     memory, streamed in chunks) at N = 2^22 so the host buffer stays at 1 GiB."""

@@ -40,6 +40,14 @@ ASSIGN_CASES = [
     (torch.float32, 2, 777, 8, 3),
     (torch.float32, 1, 500, 128, 130),
     (torch.float32, 1, 400, 40, 7),
+    # wide features (128 < d <= 512)
+    (torch.float16, 1, 3000, 256, 300),
+    (torch.bfloat16, 2, 1500, 512, 200),
+    (torch.float16, 1, 1000, 136, 70),        # first width on the wide kernel
+    (torch.float16, 1, 700, 384, 33),
+    (torch.float32, 1, 900, 256, 40),
+    (torch.float32, 1, 600, 512, 19),
+    (torch.float32, 1, 500, 200, 70),
 ]
 
 
@@ -121,6 +129,11 @@ UPDATE_CASES = [
     (torch.float16, 1, 900, 24, 2500, 0.0),       # K > N: mostly empty clusters, 2-pass sort
     (torch.float16, 1, 5000, 8, 3, 0.0),
     (torch.bfloat16, 1, 4000, 96, 50, 0.0),
+    (torch.float16, 1, 6000, 256, 40, 0.0),       # wide rows
+    (torch.bfloat16, 1, 5000, 512, 30, 0.0),
+    (torch.float32, 1, 4000, 512, 12, 0.0),       # wider than one wave-load: two column blocks
+    (torch.float32, 1, 3000, 200, 25, 0.0),
+    (torch.float16, 1, 9000, 136, 4, 0.0),
 ]
 
 
@@ -216,6 +229,7 @@ def test_lloyd_multi_iteration_call_equals_repeated_single_calls():
     (torch.float16, 40000, 128, 3000, 8192),      # two-pass sort inside every chunk
     (torch.float32, 20000, 32, 20, 20000),        # single chunk
     (torch.bfloat16, 30000, 128, 64, 0),          # chunk size chosen from the workspace
+    (torch.float16, 20000, 256, 100, 8192),       # wide features
 ])
 def test_out_of_core_equals_in_core(dtype, N, d, K, chunk):
     w, X, _, C0 = _problem(dtype, 1, N, d, K, seed=300 + N)
@@ -293,7 +307,7 @@ def test_random_shapes_full_iteration():
     dts = [torch.float16, torch.bfloat16, torch.float32]
     for case in range(40):
         dtype = dts[case % 3]
-        d = int(rng.integers(1, 17)) * 8
+        d = int(rng.integers(1, 17)) * 8 if case % 4 else int(rng.integers(17, 65)) * 8
         K = int(rng.choice([1, 2, 3, 17, 31, 32, 33, 63, 64, 65, 100, 127, 128, 129, 255, 257, 513,
                             1000, 2047, 2048, 2049, 3000]))
         N = int(rng.integers(1, 6000))
