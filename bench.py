@@ -48,6 +48,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep-variants", action="store_true",
+                    help="time the assign kernel's tile shapes exhaustively over a grid of shapes "
+                         "and compare with the shape heuristic's pick (prints one JSON line)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy first (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -69,6 +72,8 @@ def main() -> int:
     if args.workload not in short:
         print(f"unknown workload {args.workload}", file=sys.stderr)
         return 2
+    if args.sweep_variants:
+        return sweep_variants(torch, fk, dev)
     w = short[args.workload]
     steps = args.steps if args.steps is not None else w.iters
     if args.workload == "c5":
@@ -173,6 +178,49 @@ def main() -> int:
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, X, C0, torch)
     print(json.dumps(out))
+    return 0
+
+
+def sweep_variants(torch, fk, dev):
+    """Exhaustive sweep of the sweeping assign kernel's four tile shapes against the pick of
+    the shape heuristic (fk_plan), fp16, over a grid of (N, K, d)."""
+    rows = []
+    t_sweep = 0.0
+    for d in (64, 128):
+        for K in (256, 1024, 4096, 16384):
+            for N in (1 << 16, 1 << 18, 300000, 1 << 20, 1 << 22):
+                if N * K * d > 2 ** 41:
+                    continue
+                X = (torch.randn(1, N, d, device=dev) * 4).half()
+                C = (torch.randn(1, K, d, device=dev) * 4).half()
+                ws = fk.make_workspace(1, N, d, K, torch.float16, dev)
+                a = torch.empty((1, N), dtype=torch.int32, device=dev)
+                us = {}
+                for v in (0, 1, 2, 3, -1):
+                    fk.fk_set_option("assign_variant", v)
+                    t0 = time.perf_counter()
+                    for _ in range(2):
+                        fk.fk_assign(X, C, ws=ws, out=a)
+                    torch.cuda.synchronize()
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(5):
+                        fk.fk_assign(X, C, ws=ws, out=a)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    us[v] = e0.elapsed_time(e1) / 5 * 1e3
+                    if v >= 0:
+                        t_sweep += time.perf_counter() - t0
+                best = min(us[v] for v in (0, 1, 2, 3))
+                rows.append({"d": d, "K": K, "N": N, "us": {str(k): round(x, 1) for k, x in us.items()},
+                             "plan": fk.fk_plan(1, N, d, K, torch.float16).split()[0],
+                             "heuristic_over_best": round(us[-1] / best, 3)})
+    fk.fk_set_option("assign_variant", -1)
+    r = [x["heuristic_over_best"] for x in rows]
+    print(json.dumps({"metric": "assign_variant_heuristic", "shapes": len(rows),
+                      "mean_heuristic_over_best": sum(r) / len(r), "worst_heuristic_over_best": max(r),
+                      "exhaustive_sweep_seconds": t_sweep, "rows": rows}))
     return 0
 
 

@@ -144,6 +144,19 @@ fk_status fk_lloyd_ooc(const void* X_host, float* C_f32, int32_t* assign, int32_
 size_t fk_ooc_workspace_bytes(int64_t chunk_rows, int d, int K, fk_dtype t);
 
 /*
+ * Kernel-configuration choice (the counterpart of the paper's cache-aware compile heuristic,
+ * Section 4.3: a configuration is derived from the machine and the problem shape, with no
+ * tuning run).  fk_plan writes a one-line description of what the in-core entry points would
+ * launch for this shape into buf (host memory, NUL-terminated, truncated to buf_bytes):
+ * assign kernel and tile shape, sort passes and tiling, reduction granularity, workspace.
+ * Host-only.  fk_set_option("assign_variant", v) forces tile shape v in 0..3 of the sweeping
+ * assign kernel for every later call of this process (-1 = back to the heuristic); it exists
+ * so that the heuristic can be checked against an exhaustive sweep.
+ */
+int fk_plan(int B, int64_t N, int d, int K, fk_dtype t, char* buf, size_t buf_bytes);
+int fk_set_option(const char* name, int value);
+
+/*
  * Measurement aid (not a step of the method): while started, fk_lloyd_iter and fk_update
  * record a HIP event on their stream after each stage of every iteration -- assignment
  * kernel, sort-inverse, segment reduction, merge/normalise (with the centroid re-layout).

@@ -21,7 +21,7 @@ _STATUS = {0: "FK_OK", 1: "FK_EINVAL", 2: "FK_EUNSUPPORTED", 3: "FK_EWORKSPACE",
 # every symbol include/flashkm.h declares
 EXPORTS = ("fk_last_error", "fk_workspace_bytes", "fk_assign", "fk_sort_inverse", "fk_update",
            "fk_lloyd_iter", "fk_lloyd_ooc", "fk_ooc_workspace_bytes", "fk_stage_timer_start",
-           "fk_stage_timer_stop")
+           "fk_stage_timer_stop", "fk_plan", "fk_set_option")
 STAGES = ("assign", "sort", "reduce", "finalize")
 
 
@@ -60,6 +60,10 @@ def lib() -> ctypes.CDLL:
         L.fk_lloyd_iter.argtypes = [vp, vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, vp, sz, vp]
         L.fk_lloyd_ooc.restype = i32
         L.fk_lloyd_ooc.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, i32, i64, vp, sz, vp]
+        L.fk_plan.restype = i32
+        L.fk_plan.argtypes = [i32, i64, i32, i32, i32, ctypes.c_char_p, sz]
+        L.fk_set_option.restype = i32
+        L.fk_set_option.argtypes = [ctypes.c_char_p, i32]
         L.fk_stage_timer_start.restype = None
         L.fk_stage_timer_start.argtypes = []
         L.fk_stage_timer_stop.restype = i32
@@ -207,3 +211,16 @@ def fk_stage_timer_stop() -> dict:
     if rc < 0:
         raise FlashKMError(4, "stage timer: HIP event error")
     return {STAGES[i]: (float(ms[i]), int(n[i])) for i in range(4)}
+
+
+def fk_plan(B: int, N: int, d: int, K: int, dtype: torch.dtype) -> str:
+    """One-line description of the kernels and tilings chosen for this shape."""
+    buf = ctypes.create_string_buffer(512)
+    st = lib().fk_plan(B, N, d, K, _DTYPE[dtype], buf, len(buf))
+    if st not in (0, 2):
+        _check(st)
+    return buf.value.decode()
+
+
+def fk_set_option(name: str, value: int) -> None:
+    _check(lib().fk_set_option(name.encode(), int(value)))

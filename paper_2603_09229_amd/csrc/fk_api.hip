@@ -238,6 +238,47 @@ int fk_stage_timer_stop(double* stage_ms, int* stage_launches) {
     return n;
 }
 
+int fk_set_option(const char* name, int value) {
+    if (name && strcmp(name, "assign_variant") == 0 && value >= -1 && value <= 3) {
+        set_assign_variant_override(value);
+        return FK_OK;
+    }
+    set_error("fk_set_option: unknown option or value out of range");
+    return FK_EINVAL;
+}
+
+int fk_plan(int B, int64_t N, int d, int K, fk_dtype t, char* buf, size_t buf_bytes) {
+    Geometry g;
+    if (!buf || buf_bytes == 0) {
+        set_error("fk_plan: no buffer");
+        return FK_EINVAL;
+    }
+    if (!make_geometry(B, N, d, K, t, &g)) {
+        snprintf(buf, buf_bytes, "unsupported");
+        return FK_EUNSUPPORTED;
+    }
+    char assign[96];
+    const int st = (16 / g.dchunks) < 8 ? (16 / g.dchunks) : 8;
+    if (t == FK_F32)
+        snprintf(assign, sizeof(assign), "%s", g.d > 128 ? "f32_wide" : ((int64_t)B * N < (1 << 18) ? "f32_split" : "f32"));
+    else if (g.dchunks > 8)
+        snprintf(assign, sizeof(assign), "mfma_wide(chunks=%d,points_per_wg=256)", g.dchunks);
+    else if (g.ktiles <= st)
+        snprintf(assign, sizeof(assign), "mfma_stream(tiles=%d)", g.ktiles);
+    else {
+        static const int pts[4] = {256, 512, 512, 128};
+        const int v = choose_assign_variant((int64_t)B * N);
+        snprintf(assign, sizeof(assign), "mfma_sweep(variant=%d,points_per_wg=%d)", v, pts[v]);
+    }
+    snprintf(buf, buf_bytes,
+             "assign=%s ktiles=%d sort=%dpass(tile=%d,blocks=%d) reduce=%s(rows_per_item=%d) "
+             "max_items=%lld workspace=%zu",
+             assign, g.ktiles, g.sort_passes, g.sort_tile, g.sort_blocks,
+             g.waves_per_item == 4 ? "workgroup_per_item" : "wave_per_item", g.rows_per_item,
+             (long long)g.max_items, carve(g, nullptr).bytes);
+    return FK_OK;
+}
+
 size_t fk_workspace_bytes(int B, int64_t N, int d, int K, fk_dtype t) {
     Geometry g;
     if (!make_geometry(B, N, d, K, t, &g)) return 0;

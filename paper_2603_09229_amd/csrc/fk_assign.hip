@@ -788,15 +788,41 @@ static fk_status launch_mfma_v(const Geometry& g, const void* X, const void* fra
     return FK_OK;
 }
 
-// Tile shape per wave / workgroup.  FK_ASSIGN_VARIANT (read once) overrides the default for
-// experiments: 0 = 2 point tiles x 4 waves, 1 = 4 x 4, 2 = 2 x 8 (default), 3 = 1 x 4.
-static int assign_variant() {
-    static int v = [] {
-        const char* e = getenv("FK_ASSIGN_VARIANT");
-        return e ? atoi(e) : 2;
-    }();
-    return v;
+// Tile shape of the sweeping kernel (point tiles per wave x waves per workgroup):
+//   0 = 2 x 4 (256 points, 3 workgroups per CU)     1 = 4 x 4 (512 points, 2 per CU)
+//   2 = 2 x 8 (512 points, 2 per CU)                 3 = 1 x 4 (128 points, 4 per CU)
+// g_variant_override >= 0 forces one (fk_set_option / FK_ASSIGN_VARIANT); otherwise it is chosen
+// from the shape and the machine, the counterpart of the paper's cache-aware compile
+// heuristic (Section 4.3): no tuning run, just the CU count and each variant's occupancy.
+static int g_variant_override = [] {
+    const char* e = getenv("FK_ASSIGN_VARIANT");
+    return e ? atoi(e) : -1;
+}();
+
+static int device_cu_count();
+
+// Workgroups run in rounds of (CUs x workgroups per CU).  A variant is scored by how full its
+// rounds are, (W/S) / ceil(W/S) with W workgroups over S slots, times its steady-state
+// efficiency relative to the 512-point shape (bigger workgroups re-use each centroid tile
+// more, measured 1.0 / 0.95 / 0.80).  Few points -> small workgroups so the chip fills at all;
+// awkward point counts -> the shape with the least idle last round.
+int choose_assign_variant(int64_t total_points) {
+    if (g_variant_override >= 0 && g_variant_override <= 3) return g_variant_override;
+    struct V { int id, points, per_cu; double eff; };
+    static const V cand[3] = {{2, 512, 2, 1.0}, {0, 256, 3, 0.95}, {3, 128, 4, 0.80}};
+    const double cus = device_cu_count();
+    int best = 2;
+    double best_score = -1.0;
+    for (const V& v : cand) {
+        const double W = (double)cdiv(total_points, v.points), S = cus * v.per_cu;
+        const double rounds = W <= S ? 1.0 : (double)cdiv((int64_t)W, (int64_t)S);
+        const double score = v.eff * (W / S) / rounds;
+        if (score > best_score + 1e-9) { best_score = score; best = v.id; }
+    }
+    return best;
 }
+
+void set_assign_variant_override(int v) { g_variant_override = v; }
 
 // FK_ASSIGN_STREAM=0 keeps small-K shapes on the sweeping kernel (experiments).
 static bool stream_enabled() {
@@ -847,7 +873,7 @@ static fk_status launch_mfma(const Geometry& g, const void* X, const void* frag,
         FK_HIP(hipGetLastError());
         return FK_OK;
     }
-    switch (assign_variant()) {
+    switch (choose_assign_variant((int64_t)g.B * g.N)) {
         case 1: return launch_mfma_v<BF, DCH, 4, 4>(g, X, frag, bias, assign, min_dist, s);
         case 0: return launch_mfma_v<BF, DCH, 2, 4>(g, X, frag, bias, assign, min_dist, s);
         case 3: return launch_mfma_v<BF, DCH, 1, 4>(g, X, frag, bias, assign, min_dist, s);

@@ -85,6 +85,9 @@ fk_status launch_round_centroids(const Geometry& g, const float* C_f32, void* C_
 // Fused distance + online argmin.  16-bit: reads c_frag/c_bias; fp32: reads C directly.
 fk_status launch_assign(const Geometry& g, const void* X, const void* C_or_frag,
                         const float* c_bias, int32_t* assign, float* min_dist, hipStream_t s);
+// Tile shape the sweeping assign kernel would use for this many points (see fk_assign.hip).
+int choose_assign_variant(int64_t total_points);
+void set_assign_variant_override(int v);   // -1 = choose from the shape
 // Stable argsort by cluster id -> sorted_idx, seg_off (+ item_off when w.item_off != NULL).
 fk_status launch_sort_inverse(const Geometry& g, const Workspace& w, const int32_t* assign,
                               int32_t* sorted_idx, int32_t* seg_off, int32_t* item_off,

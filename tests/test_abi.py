@@ -72,3 +72,21 @@ def test_binding_rejects_host_tensors():
     X = torch.zeros((1, 8, 16), dtype=torch.float16)
     with pytest.raises(ValueError):
         fk.fk_assign(X, X[:, :2], ws=torch.empty(1024, dtype=torch.uint8))
+
+
+def test_plan_describes_the_choice_per_shape():
+    f16 = torch.float16
+    # no GPU here: the heuristic assumes 256 CUs
+    assert "mfma_sweep(variant=2" in fk.fk_plan(1, 1 << 20, 128, 1024, f16)     # whole rounds of 512
+    assert "mfma_sweep(variant=3" in fk.fk_plan(1, 1 << 16, 128, 1024, f16)     # few points: small groups
+    assert "mfma_sweep(variant=0" in fk.fk_plan(1, 300000, 128, 1024, f16)      # least idle last round
+    assert "mfma_stream" in fk.fk_plan(1, 1 << 24, 64, 16, f16)
+    assert "mfma_wide(chunks=32" in fk.fk_plan(1, 1 << 20, 512, 65536, f16)
+    assert "sort=2pass" in fk.fk_plan(1, 1 << 20, 512, 65536, f16)
+    assert "workgroup_per_item" in fk.fk_plan(1, 1 << 24, 64, 16, f16)
+    assert fk.fk_plan(1, 100, 12, 3, f16) == "unsupported"
+    fk.fk_set_option("assign_variant", 1)
+    assert "variant=1" in fk.fk_plan(1, 1 << 20, 128, 1024, f16)
+    fk.fk_set_option("assign_variant", -1)
+    with pytest.raises(fk.FlashKMError):
+        fk.fk_set_option("assign_variant", 9)
