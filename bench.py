@@ -51,6 +51,9 @@ def main() -> int:
     ap.add_argument("--sweep-variants", action="store_true",
                     help="time the assign kernel's tile shapes exhaustively over a grid of shapes "
                          "and compare with the shape heuristic's pick (prints one JSON line)")
+    ap.add_argument("--compare-standard", action="store_true",
+                    help="time the fused assign and the sort-inverse update against the standard "
+                         "implementation (materialised distances, atomic scatter) on a few shapes")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy first (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -74,6 +77,8 @@ def main() -> int:
         return 2
     if args.sweep_variants:
         return sweep_variants(torch, fk, dev)
+    if args.compare_standard:
+        return compare_standard(torch, fk, wl, dev)
     w = short[args.workload]
     steps = args.steps if args.steps is not None else w.iters
     if args.workload == "c5":
@@ -177,6 +182,56 @@ def main() -> int:
     # ---------------------------------------------------------------- CPU oracle baseline
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, X, C0, torch)
+    print(json.dumps(out))
+    return 0
+
+
+def _time_us(torch, fn, reps=5):
+    fn()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps * 1e3
+
+
+def compare_standard(torch, fk, wl, dev):
+    """Kernel-level comparison of the paper's Section 5.2 on this machine: fused assign vs
+    distance-matrix + argmin, sort-inverse update vs atomic scatter (fp16, Gaussian mixtures)."""
+    out = {"metric": "kernel_level_comparison", "assign": [], "update": []}
+    for (N, K, d) in [(1 << 16, 1024, 128), (1 << 20, 1024, 128), (1 << 20, 8192, 128), (1 << 18, 65536, 128)]:
+        w = wl.C2.scaled(N=N, K=K, d=d)
+        X = wl.make_points(w, device=dev)
+        C = wl.gather_rows(X, wl.init_rows(w)).to(torch.float16)
+        ws = fk.make_workspace(1, N, d, K, torch.float16, dev)
+        D = torch.empty((1, N, K), dtype=torch.float32, device=dev)
+        a = torch.empty((1, N), dtype=torch.int32, device=dev)
+        t_fused = _time_us(torch, lambda: fk.fk_assign(X, C, ws=ws, out=a))
+        t_std = _time_us(torch, lambda: fk.fk_standard_assign(X, C, D=D, ws=ws))
+        a2, _ = fk.fk_standard_assign(X, C, D=D, ws=ws)
+        same = float((a2 == fk.fk_assign(X, C, ws=ws)).float().mean())
+        out["assign"].append({"N": N, "K": K, "d": d, "fused_us": t_fused, "standard_us": t_std,
+                              "speedup": t_std / t_fused, "distance_matrix_bytes": 4 * N * K,
+                              "same_assignment_fraction": same})
+        del D, X
+    for (N, K, d, zipf) in [(1 << 20, 1024, 128, 0.0), (1 << 25, 4096, 128, 0.0), (1 << 24, 16, 64, 1.2)]:
+        w = wl.C2.scaled(N=N, K=K, d=d, zipf_s=zipf)
+        X, lab = wl.make_points(w, device=dev, return_labels=True)
+        C = torch.zeros((1, K, d), dtype=torch.float32, device=dev)
+        ws = fk.make_workspace(1, N, d, K, torch.float16, dev)
+        sums = torch.empty((1, K, d), dtype=torch.float32, device=dev)
+        t_si = _time_us(torch, lambda: fk.fk_update(X, lab, C, ws=ws))
+        t_at = _time_us(torch, lambda: fk.fk_standard_update(X, lab, C, sums=sums))
+        nbytes = N * (d * 2 + 12)
+        out["update"].append({"N": N, "K": K, "d": d, "zipf_s": zipf, "sort_inverse_us": t_si,
+                              "atomic_scatter_us": t_at, "speedup": t_at / t_si,
+                              "sort_inverse_gbps": nbytes / t_si / 1e3,
+                              "atomic_scatter_gbps": N * (d * 2 + 4) / t_at / 1e3})
+        del X, lab
     print(json.dumps(out))
     return 0
 

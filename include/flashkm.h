@@ -144,6 +144,26 @@ fk_status fk_lloyd_ooc(const void* X_host, float* C_f32, int32_t* assign, int32_
 size_t fk_ooc_workspace_bytes(int64_t chunk_rows, int d, int K, fk_dtype t);
 
 /*
+ * Comparator only: the standard implementation the paper starts from (Section 3.1,
+ * Algorithm 1).  Not used by any entry point above; built to measure, on this machine, what
+ * the fused assignment and the sort-inverse update are compared against in the paper's
+ * Section 5.2.
+ *   fk_standard_assign  Kernel 1 writes D[B,N,K] (float, device, caller-provided: N*K*4 bytes
+ *                       per instance) = ||x||^2 + ||c||^2 - 2 x.c with the x.c contraction on
+ *                       MFMA; Kernel 2 reads D back and takes the row argmin.  fp16 / bf16,
+ *                       d <= 128.  C is [B,K,d] of dtype t; ws as for fk_assign.
+ *   fk_standard_update  Kernel 3 adds every point's features and a count into sums[B,K,d] /
+ *                       counts[B,K] with atomics (order not reproducible); Kernel 4 divides.
+ *                       sums is device scratch provided by the caller.  Any dtype, d <= 512.
+ */
+fk_status fk_standard_assign(const void* X, const void* C, float* D, int32_t* assign, int B,
+                             int64_t N, int d, int K, fk_dtype t, void* ws, size_t ws_bytes,
+                             void* stream);
+fk_status fk_standard_update(const void* X, const int32_t* assign, const float* C_prev_f32,
+                             float* C_out_f32, int32_t* counts, float* sums, int B, int64_t N,
+                             int d, int K, fk_dtype t, void* stream);
+
+/*
  * Kernel-configuration choice (the counterpart of the paper's cache-aware compile heuristic,
  * Section 4.3: a configuration is derived from the machine and the problem shape, with no
  * tuning run).  fk_plan writes a one-line description of what the in-core entry points would

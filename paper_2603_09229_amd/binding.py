@@ -21,7 +21,8 @@ _STATUS = {0: "FK_OK", 1: "FK_EINVAL", 2: "FK_EUNSUPPORTED", 3: "FK_EWORKSPACE",
 # every symbol include/flashkm.h declares
 EXPORTS = ("fk_last_error", "fk_workspace_bytes", "fk_assign", "fk_sort_inverse", "fk_update",
            "fk_lloyd_iter", "fk_lloyd_ooc", "fk_ooc_workspace_bytes", "fk_stage_timer_start",
-           "fk_stage_timer_stop", "fk_plan", "fk_set_option")
+           "fk_stage_timer_stop", "fk_plan", "fk_set_option", "fk_standard_assign",
+           "fk_standard_update")
 STAGES = ("assign", "sort", "reduce", "finalize")
 
 
@@ -60,6 +61,10 @@ def lib() -> ctypes.CDLL:
         L.fk_lloyd_iter.argtypes = [vp, vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, vp, sz, vp]
         L.fk_lloyd_ooc.restype = i32
         L.fk_lloyd_ooc.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, i32, i64, vp, sz, vp]
+        L.fk_standard_assign.restype = i32
+        L.fk_standard_assign.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, vp, sz, vp]
+        L.fk_standard_update.restype = i32
+        L.fk_standard_update.argtypes = [vp, vp, vp, vp, vp, vp, i32, i64, i32, i32, i32, vp]
         L.fk_plan.restype = i32
         L.fk_plan.argtypes = [i32, i64, i32, i32, i32, ctypes.c_char_p, sz]
         L.fk_set_option.restype = i32
@@ -224,3 +229,36 @@ def fk_plan(B: int, N: int, d: int, K: int, dtype: torch.dtype) -> str:
 
 def fk_set_option(name: str, value: int) -> None:
     _check(lib().fk_set_option(name.encode(), int(value)))
+
+
+def fk_standard_assign(X, C, *, D=None, ws=None):
+    """Comparator (paper Algorithm 1, kernels 1-2): materialises D [B,N,K] float32, then argmin.
+
+    -> (assign [B,N] int32, D)."""
+    B, N, d, K = _shape3(X, C)
+    _dev(X, "X"); _dev(C, "C", X.dtype)
+    ws = ws if ws is not None else make_workspace(B, N, d, K, X.dtype, X.device)
+    if D is None:
+        D = torch.empty((B, N, K), dtype=torch.float32, device=X.device)
+    _dev(D, "D", torch.float32, (B, N, K))
+    a = torch.empty((B, N), dtype=torch.int32, device=X.device)
+    _check(lib().fk_standard_assign(_ptr(X), _ptr(C), _ptr(D), _ptr(a), B, N, d, K, _DTYPE[X.dtype],
+                                    _ptr(ws), ws.numel(), _stream(X.device)))
+    return a, D
+
+
+def fk_standard_update(X, assign, C_prev_f32, *, sums=None):
+    """Comparator (paper Algorithm 1, kernels 3-4): atomic scatter, then normalise.
+
+    -> (C_f32 [B,K,d], counts [B,K] int32)."""
+    B, N, d, K = _shape3(X, C_prev_f32)
+    _dev(X, "X"); _dev(assign, "assign", torch.int32, (B, N))
+    _dev(C_prev_f32, "C_prev_f32", torch.float32)
+    if sums is None:
+        sums = torch.empty((B, K, d), dtype=torch.float32, device=X.device)
+    C_out = torch.empty_like(C_prev_f32)
+    counts = torch.empty((B, K), dtype=torch.int32, device=X.device)
+    _check(lib().fk_standard_update(_ptr(X), _ptr(assign), _ptr(C_prev_f32), _ptr(C_out),
+                                    _ptr(counts), _ptr(sums), B, N, d, K, _DTYPE[X.dtype],
+                                    _stream(X.device)))
+    return C_out, counts

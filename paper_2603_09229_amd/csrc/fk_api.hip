@@ -354,6 +354,37 @@ fk_status fk_update(const void* X, const int32_t* assign, const float* C_prev_f3
     return run_update(g, w, X, assign, fa, (hipStream_t)stream);
 }
 
+fk_status fk_standard_assign(const void* X, const void* C, float* D, int32_t* assign, int B,
+                             int64_t N, int d, int K, fk_dtype t, void* ws, size_t ws_bytes,
+                             void* stream) {
+    Geometry g;
+    FK_TRY(check_common("fk_standard_assign", B, N, d, K, t, ws, ws_bytes, &g));
+    FK_REQUIRE_PTR("fk_standard_assign", X);
+    FK_REQUIRE_PTR("fk_standard_assign", C);
+    FK_REQUIRE_PTR("fk_standard_assign", D);
+    FK_REQUIRE_PTR("fk_standard_assign", assign);
+    const Workspace w = carve(g, ws);
+    return launch_standard_assign(g, w, X, C, D, assign, (hipStream_t)stream);
+}
+
+fk_status fk_standard_update(const void* X, const int32_t* assign, const float* C_prev_f32,
+                             float* C_out_f32, int32_t* counts, float* sums, int B, int64_t N,
+                             int d, int K, fk_dtype t, void* stream) {
+    Geometry g;
+    if (!make_geometry(B, N, d, K, t, &g)) {
+        set_error("fk_standard_update: unsupported shape B=%d N=%lld d=%d K=%d", B, (long long)N, d, K);
+        return FK_EUNSUPPORTED;
+    }
+    FK_REQUIRE_PTR("fk_standard_update", X);
+    FK_REQUIRE_PTR("fk_standard_update", assign);
+    FK_REQUIRE_PTR("fk_standard_update", C_prev_f32);
+    FK_REQUIRE_PTR("fk_standard_update", C_out_f32);
+    FK_REQUIRE_PTR("fk_standard_update", counts);
+    FK_REQUIRE_PTR("fk_standard_update", sums);
+    return launch_standard_update(g, X, assign, C_prev_f32, C_out_f32, counts, sums,
+                                  (hipStream_t)stream);
+}
+
 fk_status fk_lloyd_iter(const void* X, float* C_f32, void* C_lp, int32_t* assign,
                         int32_t* counts, int B, int64_t N, int d, int K, fk_dtype t, int iters,
                         void* ws, size_t ws_bytes, void* stream) {

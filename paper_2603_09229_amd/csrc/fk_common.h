@@ -112,4 +112,11 @@ struct FinalizeArgs {
 fk_status launch_finalize(const Geometry& g, const Workspace& w, const int32_t* seg_off,
                           const int32_t* item_off, const FinalizeArgs& a, hipStream_t s);
 
+// Comparator: the standard implementation (paper Algorithm 1); see fk_standard.hip.
+fk_status launch_standard_assign(const Geometry& g, const Workspace& w, const void* X,
+                                 const void* C_lp, float* D, int32_t* assign, hipStream_t s);
+fk_status launch_standard_update(const Geometry& g, const void* X, const int32_t* assign,
+                                 const float* C_prev, float* C_out, int32_t* counts, float* sums,
+                                 hipStream_t s);
+
 }  // namespace fk

@@ -327,3 +327,34 @@ def test_random_shapes_full_iteration():
             parity.check_update(Xb, a[b].cpu().numpy(), C0[b].numpy(), C[b].cpu().numpy(),
                                 counts[b].cpu().numpy(), parity.CENTROID_TOL[dtype])
         assert torch.equal(C_lp.cpu(), C.cpu().to(dtype)), (case, dtype, B, N, d, K)
+
+
+@pytest.mark.parametrize("dtype,B,N,d,K", [(torch.float16, 1, 3000, 128, 300), (torch.bfloat16, 2, 1000, 64, 37),
+                                           (torch.float16, 1, 700, 24, 5)])
+def test_standard_comparator_assign(dtype, B, N, d, K):
+    """The materialising comparator (Algorithm 1, kernels 1-2) obeys the same parity rule, and
+    its distance matrix is the squared distances."""
+    w, X, _, C0 = _problem(dtype, B, N, d, K, seed=700 + N)
+    C = C0.to(dtype)
+    a, D = fk.fk_standard_assign(X.to(DEV), C.to(DEV))
+    torch.cuda.synchronize()
+    for b in range(B):
+        Xb, Cb = parity.widen(X[b]), parity.widen(C[b])
+        parity.check_assign(Xb, Cb, a[b].cpu().numpy())
+        ref = ((Xb[:50, None, :].astype(np.float64) - Cb[None].astype(np.float64)) ** 2).sum(-1)
+        scale = (Xb[:50].astype(np.float64) ** 2).sum(1)[:, None] + (Cb.astype(np.float64) ** 2).sum(1)[None]
+        assert (np.abs(D[b, :50].cpu().numpy() - ref) <= 1e-3 * scale + 1e-5).all()
+
+
+@pytest.mark.parametrize("dtype,B,N,d,K", [(torch.float16, 1, 20000, 128, 64), (torch.float32, 2, 3000, 40, 9),
+                                           (torch.bfloat16, 1, 5000, 256, 12)])
+def test_standard_comparator_update(dtype, B, N, d, K):
+    w, X, lab, C0 = _problem(dtype, B, N, d, K, seed=800 + N)
+    a = lab.clone()
+    if K > 4:
+        a[a == 1] = 0
+    C_new, counts = fk.fk_standard_update(X.to(DEV), a.to(DEV), C0.to(DEV))
+    torch.cuda.synchronize()
+    for b in range(B):
+        parity.check_update(parity.widen(X[b]), a[b].numpy(), C0[b].numpy(), C_new[b].cpu().numpy(),
+                            counts[b].cpu().numpy(), parity.CENTROID_TOL[dtype] * (1 if dtype != torch.float32 else 10))
