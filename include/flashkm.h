@@ -24,7 +24,9 @@
  *   - Inputs must be finite; for FK_F16 twice the largest centroid norm must stay finite
  *     in fp32 (always true for fp16 data).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
- *     enqueue work on it and return without waiting, except fk_lloyd_ooc.
+ *     enqueue work on it and return without waiting, except fk_lloyd_ooc.  The in-core calls
+ *     enqueue kernels only (no memset, no allocation), so after one eager call for a shape
+ *     they can be recorded into a HIP graph by stream capture and replayed.
  *   - Supported shapes: 1 <= K <= 65536, 1 <= N, B*N < 2^31, B >= 1,
  *     d a multiple of 8 with 8 <= d <= 512.  Anything else returns FK_EUNSUPPORTED or
  *     FK_EINVAL; there is no fallback path.

@@ -861,9 +861,16 @@ static fk_status launch_mfma(const Geometry& g, const void* X, const void* frag,
             FK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
             attr_set[one_tile] = true;
         }
-        int per_cu = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, WAVES * 64, lds) != hipSuccess || per_cu < 1)
-            per_cu = 1;
+        // queried once per kernel (also keeps the launch path free of runtime queries, so
+        // that it can be captured into a HIP graph after one eager call)
+        static int per_cu_cache[2] = {0, 0};
+        if (per_cu_cache[one_tile] == 0) {
+            int q = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&q, kern, WAVES * 64, lds) != hipSuccess || q < 1)
+                q = 1;
+            per_cu_cache[one_tile] = q;
+        }
+        const int per_cu = per_cu_cache[one_tile];
         const int64_t nbatches = cdiv(g.N, 32);
         int64_t wgs = (int64_t)device_cu_count() * per_cu;
         if (wgs > cdiv(nbatches, WAVES)) wgs = cdiv(nbatches, WAVES);

@@ -358,3 +358,34 @@ def test_standard_comparator_update(dtype, B, N, d, K):
     for b in range(B):
         parity.check_update(parity.widen(X[b]), a[b].numpy(), C0[b].numpy(), C_new[b].cpu().numpy(),
                             counts[b].cpu().numpy(), parity.CENTROID_TOL[dtype] * (1 if dtype != torch.float32 else 10))
+
+
+@pytest.mark.parametrize("dtype,N,d,K", [(torch.float16, 30000, 128, 300), (torch.float16, 40000, 64, 16),
+                                         (torch.float32, 5000, 64, 20)])
+def test_iteration_replays_from_a_hip_graph(dtype, N, d, K):
+    """The library allocates nothing and enqueues kernels only, so one iteration can be captured
+    into a graph and replayed.  Replays are interleaved with eager work and each is compared
+    with the eager result of the same step."""
+    w, X, _, C0 = _problem(dtype, 1, N, d, K, seed=900 + N)
+    Xd = X.to(DEV)
+    ws = fk.make_workspace(1, N, d, K, dtype, DEV)
+    C_g = C0.to(DEV).clone()
+    a_g = torch.empty((1, N), dtype=torch.int32, device=DEV)
+    n_g = torch.empty((1, K), dtype=torch.int32, device=DEV)
+    lp_g = torch.empty((1, K, d), dtype=dtype, device=DEV)
+    # one eager call first: one-time kernel attribute / occupancy queries happen here
+    fk.fk_lloyd_iter(Xd, C_g, 1, ws=ws, C_lp=lp_g, assign=a_g, counts=n_g)
+    C_g.copy_(C0.to(DEV))
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fk.fk_lloyd_iter(Xd, C_g, 1, ws=ws, C_lp=lp_g, assign=a_g, counts=n_g)
+    C_g.copy_(C0.to(DEV))
+    C_e = C0.to(DEV).clone()
+    ws_e = fk.make_workspace(1, N, d, K, dtype, DEV)
+    for step in range(4):
+        graph.replay()
+        a_e, n_e, lp_e = fk.fk_lloyd_iter(Xd, C_e, 1, ws=ws_e)     # eager, same step
+        torch.cuda.synchronize()
+        assert torch.equal(C_g, C_e) and torch.equal(a_g, a_e) and torch.equal(n_g, n_e), step
+        assert torch.equal(lp_g, lp_e)
