@@ -105,7 +105,12 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_hist_kernel(
     const int b = blockIdx.y, blk = blockIdx.x, nb = gridDim.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     keys += (size_t)b * N;
-    for (int i = tid; i < NB; i += kSortThreads) hist[i] = 0;
+    // Few bins: hot bins would serialise the LDS adds of a wave (lanes hitting one address are
+    // processed one after the other), so each group of lanes (lane % 16) counts into its own
+    // copy of the histogram and the copies are added at the end.
+    const int copies = NB <= 64 ? 16 : 1;
+    int* my_hist = hist + (copies > 1 ? (lane & 15) * NB : 0);
+    for (int i = tid; i < NB * copies; i += kSortThreads) hist[i] = 0;
     __syncthreads();
     // rounds are software-pipelined: the next round's keys are requested before this round's
     // are counted
@@ -116,19 +121,21 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_hist_kernel(
         const int64_t nbase = base0 + (int64_t)(r + 1) * kSubTile;
         const bool more = r + 1 < rounds && nbase < N;
         if (more) load_round(keys, nbase, N, lane, kmax, kn);
-        // one LDS add per key: lanes that hit the same bin are serialised by the LDS unit, a
-        // few tens of cycles per instruction even for very hot bins, far cheaper than
-        // resolving the duplicates with ballots first
+        // one LDS add per key (cheaper than resolving duplicates with ballots first)
 #pragma unroll
         for (int j = 0; j < kBatches; ++j)
-            if (k[j] >= 0) atomicAdd(&hist[(k[j] >> shift) & mask], 1);
+            if (k[j] >= 0) atomicAdd(&my_hist[(k[j] >> shift) & mask], 1);
         if (!more) break;
 #pragma unroll
         for (int j = 0; j < kBatches; ++j) k[j] = kn[j];
     }
     __syncthreads();
     int32_t* out = H + (size_t)b * NB * nb + blk;
-    for (int i = tid; i < NB; i += kSortThreads) out[(size_t)i * nb] = hist[i];
+    for (int i = tid; i < NB; i += kSortThreads) {
+        int c = 0;
+        for (int q = 0; q < copies; ++q) c += hist[q * NB + i];
+        out[(size_t)i * nb] = c;
+    }
 }
 
 // Exclusive scan of H[b][bin][0..nb) in place; tot[b][bin] = row sum.  TPB threads (one wave,
@@ -347,11 +354,12 @@ static fk_status sort_pass(const Geometry& g, const Workspace& w, const int32_t*
     int32_t* tot = w.digit_off;
     dim3 grid(g.sort_blocks, g.B);
     const bool wide = NB > 1024;       // 8 waves of counters would not fit in LDS
+    const size_t hist_lds = (size_t)NB * (NB <= 64 ? 16 : 1) * sizeof(int);
     if (wide)
-        hipLaunchKernelGGL(sort_hist_kernel<4>, grid, dim3(256), NB * sizeof(int), s, keys, H, g.N,
+        hipLaunchKernelGGL(sort_hist_kernel<4>, grid, dim3(256), hist_lds, s, keys, H, g.N,
                            rounds, NB, shift, mask, g.K - 1, nbits);
     else
-        hipLaunchKernelGGL(sort_hist_kernel<8>, grid, dim3(512), NB * sizeof(int), s, keys, H, g.N,
+        hipLaunchKernelGGL(sort_hist_kernel<8>, grid, dim3(512), hist_lds, s, keys, H, g.N,
                            rounds, NB, shift, mask, g.K - 1, nbits);
     FK_HIP(hipGetLastError());
     if (g.sort_blocks > 512)
