@@ -54,6 +54,9 @@ def main() -> int:
     ap.add_argument("--compare-standard", action="store_true",
                     help="time the fused assign and the sort-inverse update against the standard "
                          "implementation (materialised distances, atomic scatter) on a few shapes")
+    ap.add_argument("--general-update", action="store_true",
+                    help="few-cluster shapes: use the general assign + sort-inverse path instead "
+                         "of the fused one-hot pass (for comparing the two)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy first (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -79,6 +82,8 @@ def main() -> int:
         return sweep_variants(torch, fk, dev)
     if args.compare_standard:
         return compare_standard(torch, fk, wl, dev)
+    if args.general_update:
+        fk.fk_set_option("fused_update", 0)
     w = short[args.workload]
     steps = args.steps if args.steps is not None else w.iters
     if args.workload == "c5":
@@ -129,6 +134,9 @@ def main() -> int:
 
     es = 4 if w.dtype == "fp32" else 2
     flops = 2.0 * w.B * w.N * w.K * w.d
+    fused = "stream_update" in fk.fk_plan(w.B, w.N, w.d, w.K, w.torch_dtype)
+    if fused:
+        return report_fused(args, w, steps, ms_per_step, avg, es, flops, X, C0, torch)
     assign_tflops = flops / (avg["assign"] * 1e-3) / 1e12
     assign_bytes = w.B * (w.N * w.d * es + w.K * w.d * es + 4 * w.K + 4 * w.N)
     upd_bytes = w.B * (w.N * (w.d * es + 12) + w.K * w.d * (4 + es))
@@ -180,6 +188,38 @@ def main() -> int:
     }
 
     # ---------------------------------------------------------------- CPU oracle baseline
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, X, C0, torch)
+    print(json.dumps(out))
+    return 0
+
+
+def report_fused(args, w, steps, ms_per_step, avg, es, flops, X, C0, torch):
+    """Few clusters: assignment and sums come out of ONE streaming pass over X (the stage timer
+    books it under "assign"; there is no sort and no gather), followed by the merge/normalise.
+    The pass is HBM-bound; its algorithmic bytes are X and C read once and the assignment
+    written once."""
+    pass_bytes = w.B * (w.N * w.d * es + w.K * w.d * es + 4 * w.K + 4 * w.N)
+    g = pass_bytes / (avg["assign"] * 1e-3) / 1e9
+    out = {
+        "metric": "lloyd_iterations_per_s",
+        "value": 1e3 / ms_per_step,
+        "unit": "iterations/s",
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"fp16": "f16", "bf16": "bf16"}[w.dtype],
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "N": w.N, "d": w.d, "K": w.K,
+                   "storage": w.dtype, "accumulate": "f32", "update": "fused one-hot MFMA pass"},
+        "assign_tflops": flops / (avg["assign"] * 1e-3) / 1e12,
+        "fused_pass_gbps": g,
+        "stage_ms": avg,
+        "roofline": {"kernel": "stream_update_kernel", "bound": "hbm", "achieved": g,
+                     "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": g / PEAK_HBM_GBPS,
+                     "traffic": _traffic_from_profiles("stream_update_kernel", w.name),
+                     "avg_launch_ms": avg["assign"]},
+    }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, X, C0, torch)
     print(json.dumps(out))

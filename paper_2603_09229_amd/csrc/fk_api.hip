@@ -4,6 +4,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <algorithm>
 #include <vector>
 
 #include "fk_common.h"
@@ -87,6 +88,10 @@ bool make_geometry(int B, int64_t N, int d, int K, fk_dtype t, Geometry* g) {
     if (N > ((int64_t)1 << 22)) { R = cdiv(N, 4096); g->waves_per_item = 4; }
     g->rows_per_item = (int)R;
     g->max_items = N / R + K;
+    // never more workgroups than there are groups of four 32-point batches
+    g->fused_grid_cap = 0;
+    if (t != FK_F32 && K <= 32 && d <= 128)
+        g->fused_grid_cap = (int)std::min<int64_t>(B >= 1024 ? 1 : 1024 / B, cdiv(cdiv(N, 32), 4));
     return true;
 }
 
@@ -122,7 +127,9 @@ Workspace carve(const Geometry& g, void* base) {
         w.c_frag = take((size_t)g.B * g.ktiles * g.dchunks * 64 * 16);
         w.c_bias = (float*)take((size_t)g.B * g.ktiles * 32 * 4);
     }
-    w.partial = (float*)take((size_t)g.B * (size_t)g.max_items * g.d * 4);
+    const size_t fused_rows = (size_t)g.K * g.fused_grid_cap;
+    w.partial = (float*)take((size_t)g.B * std::max((size_t)g.max_items, fused_rows) * g.d * 4);
+    if (g.fused_grid_cap > 0) w.wg_counts = (int32_t*)take((size_t)g.B * fused_rows * 4);
     w.sums = (float*)take(BKd * 4);
     w.bytes = off;
     return w;
@@ -183,15 +190,26 @@ static fk_status check_common(const char* fn, int B, int64_t N, int d, int K, fk
             return FK_EINVAL;                                                      \
         }                                                                          \
     } while (0)
-#define FK_TRY(expr)                       \
-    do {                                   \
-        fk_status _s = (expr);             \
-        if (_s != FK_OK) return _s;        \
-    } while (0)
+
+// few clusters: one streaming pass over X builds per-workgroup tables of sums (computing the
+// assignment on the way when asked to), then the usual merge/normalise
+static fk_status run_stream_update(const Geometry& g, const Workspace& w, const void* X,
+                                   int32_t* assign, bool compute_assign, const FinalizeArgs& fa,
+                                   hipStream_t s) {
+    int G = 0;
+    FK_TRY(launch_stream_update(g, w, X, assign, compute_assign, &G, s));
+    timer_mark(s, compute_assign ? kStageAssign : kStageReduce);
+    Geometry gm = g;
+    gm.max_items = (int64_t)g.K * G;       // partial rows per instance as that pass wrote them
+    FK_TRY(launch_finalize(gm, w, nullptr, nullptr, fa, s, w.wg_counts, G));
+    timer_mark(s, kStageFinalize);
+    return FK_OK;
+}
 
 // update = sort-inverse + segment reduce + merge/normalise, all into the carved workspace
 static fk_status run_update(const Geometry& g, const Workspace& w, const void* X,
                             const int32_t* assign, const FinalizeArgs& fa, hipStream_t s) {
+    if (fused_update_enabled(g)) return run_stream_update(g, w, X, (int32_t*)assign, false, fa, s);
     FK_TRY(launch_sort_inverse(g, w, assign, w.sorted_idx, w.seg_off, w.item_off, s));
     timer_mark(s, kStageSort);
     FK_TRY(launch_segment_reduce(g, w, X, w.sorted_idx, w.seg_off, w.item_off, s));
@@ -243,6 +261,10 @@ int fk_set_option(const char* name, int value) {
         set_assign_variant_override(value);
         return FK_OK;
     }
+    if (name && strcmp(name, "fused_update") == 0 && value >= -1 && value <= 1) {
+        set_fused_update_option(value);
+        return FK_OK;
+    }
     set_error("fk_set_option: unknown option or value out of range");
     return FK_EINVAL;
 }
@@ -269,6 +291,13 @@ int fk_plan(int B, int64_t N, int d, int K, fk_dtype t, char* buf, size_t buf_by
         static const int pts[4] = {256, 512, 512, 128};
         const int v = choose_assign_variant((int64_t)B * N);
         snprintf(assign, sizeof(assign), "mfma_sweep(variant=%d,points_per_wg=%d)", v, pts[v]);
+    }
+    if (fused_update_enabled(g)) {
+        snprintf(buf, buf_bytes,
+                 "assign+update=stream_update(one-hot MFMA, X read once per iteration, no sort; "
+                 "at most %d workgroups per instance) fk_assign alone=%s workspace=%zu",
+                 g.fused_grid_cap, assign, carve(g, nullptr).bytes);
+        return FK_OK;
     }
     snprintf(buf, buf_bytes,
              "assign=%s ktiles=%d sort=%dpass(tile=%d,blocks=%d) reduce=%s(rows_per_item=%d) "
@@ -407,11 +436,15 @@ fk_status fk_lloyd_iter(const void* X, float* C_f32, void* C_lp, int32_t* assign
     FK_TRY(launch_round_centroids(g, C_f32, t == FK_F32 ? nullptr : lp, w.c_frag, w.c_bias, s));
     for (int it = 0; it < iters; ++it) {
         timer_mark(s, -1);
-        if (t == FK_F32)
-            FK_TRY(launch_assign(g, X, C_f32, nullptr, assign, nullptr, s));
-        else
-            FK_TRY(launch_assign(g, X, w.c_frag, w.c_bias, assign, nullptr, s));
-        timer_mark(s, kStageAssign);
+        // few clusters: assignment and sums in one pass over X (see run_stream_update)
+        const bool fused = fused_update_enabled(g);
+        if (!fused) {
+            if (t == FK_F32)
+                FK_TRY(launch_assign(g, X, C_f32, nullptr, assign, nullptr, s));
+            else
+                FK_TRY(launch_assign(g, X, w.c_frag, w.c_bias, assign, nullptr, s));
+            timer_mark(s, kStageAssign);
+        }
         FinalizeArgs fa;
         fa.C_prev_f32 = C_f32;
         fa.C_out_f32 = C_f32;
@@ -422,7 +455,11 @@ fk_status fk_lloyd_iter(const void* X, float* C_f32, void* C_lp, int32_t* assign
         fa.sums = nullptr;
         fa.accumulate = false;
         fa.normalise = true;
-        FK_TRY(run_update(g, w, X, assign, fa, s));
+        if (fused) {
+            FK_TRY(run_stream_update(g, w, X, assign, true, fa, s));
+        } else {
+            FK_TRY(run_update(g, w, X, assign, fa, s));
+        }
     }
     return FK_OK;
 }

@@ -471,7 +471,6 @@ __global__ __launch_bounds__(WAVES * 64) void assign_mfma_stream_kernel(
     __shared__ float sbias[KT * 32];
     extern __shared__ uintx4 dyn_lds[];                // per wave: a ring of 3 batch buffers
     const int ppr = d >> 3;                            // 16-byte pieces per row
-    const int slots = kRows * ppr;                     // pieces per batch
     constexpr int loads = DCH;                         // load instructions per batch (some may be empty)
     const int swz = (ppr & (ppr - 1)) == 0 ? min(ppr, 8) - 1 : 0;   // XOR mask for the piece index
 
@@ -493,16 +492,22 @@ __global__ __launch_bounds__(WAVES * 64) void assign_mfma_stream_kernel(
     const int64_t stride = (int64_t)gridDim.x * WAVES;
     int64_t t = (int64_t)blockIdx.x * WAVES + wave;
 
-    // slot j of the buffer holds piece (j % ppr) ^ (row & swz) of row j / ppr
+    // Slot j of the buffer holds piece (j % ppr) ^ (row & swz) of row j / ppr.  Every copy
+    // instruction is issued with all lanes live -- slots past the end of the batch or of X
+    // re-read the last valid row into buffer space nobody reads -- because the waits below
+    // count instructions: one skipped for want of live lanes would let an older copy slip
+    // past the wait.
     auto request = [&](int64_t batch, uintx4* buf) {
+#pragma unroll
         for (int q = 0; q < loads; ++q) {
             const int j = q * 64 + lane;
-            const int row = j / ppr, piece = (j - row * ppr) ^ (row & swz);
-            const int64_t point = batch * kRows + row;
-            if (j < slots && point < N)
-                __builtin_amdgcn_global_load_lds(
-                    (const __attribute__((address_space(1))) void*)(X + (size_t)point * d + piece * 8),
-                    (__attribute__((address_space(3))) void*)(buf + q * 64), 16, 0, 0);
+            int row = j / ppr;
+            const int piece = (j - row * ppr) ^ (row & swz);
+            row = min(row, kRows - 1);
+            const int64_t point = min(batch * kRows + row, N - 1);
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(X + (size_t)point * d + piece * 8),
+                (__attribute__((address_space(3))) void*)(buf + q * 64), 16, 0, 0);
         }
     };
 

@@ -19,6 +19,12 @@ fk_status hip_fail(hipError_t e, const char* what);
         if (_e != hipSuccess) return fk::hip_fail(_e, #call);  \
     } while (0)
 
+#define FK_TRY(expr)                       \
+    do {                                   \
+        fk_status _s = (expr);             \
+        if (_s != FK_OK) return _s;        \
+    } while (0)
+
 // ---------------------------------------------------------------- small helpers
 constexpr int kWave = 64;
 
@@ -49,6 +55,9 @@ struct Geometry {
     int rows_per_item;   // R: sorted positions reduced into one partial row
     int waves_per_item;  // 1, or 4 (a whole workgroup) for the long items of few-cluster shapes
     int64_t max_items;   // upper bound on sum_k ceil(n_k / R) per instance
+    // sort-free update for few clusters (16-bit storage, K <= 32, d <= 128): most workgroups
+    // per instance it may use, 0 when the shape is not eligible
+    int fused_grid_cap;
 };
 
 // Carved device workspace (all pointers 256-byte aligned inside the caller's buffer).
@@ -64,7 +73,8 @@ struct Workspace {
     int32_t* keys_tmp;   // [B,N] keys after pass 1 (two-pass sort only)
     int32_t* vals_tmp;   // [B,N] values after pass 1 (two-pass sort only)
     int32_t* keys_sorted;// [B,N] sorted keys (two-pass sort only)
-    float* partial;      // [B,max_items,d] per-item segment sums
+    float* partial;      // [B,max(max_items, K*fused_grid_cap),d] per-item segment sums
+    int32_t* wg_counts;  // [B,K,fused_grid_cap] per-workgroup counts (few-cluster update only)
     float* sums;         // [B,K,d] accumulated sums (chunked mode)
     size_t bytes;        // total bytes carved
 };
@@ -109,8 +119,21 @@ struct FinalizeArgs {
     bool accumulate;     // add onto sums / counts already there
     bool normalise;      // divide and write centroids
 };
+// With wg_counts (few-cluster path) cluster k owns partial rows [k*G, (k+1)*G) and the counts
+// wg_counts[b][k][0..G) instead of what seg_off / item_off say (those may then be NULL).
 fk_status launch_finalize(const Geometry& g, const Workspace& w, const int32_t* seg_off,
-                          const int32_t* item_off, const FinalizeArgs& a, hipStream_t s);
+                          const int32_t* item_off, const FinalizeArgs& a, hipStream_t s,
+                          const int32_t* wg_counts = nullptr, int wg_per_cluster = 0);
+
+// Few clusters: stream X once, add every 32-point batch into per-workgroup K x d tables with a
+// one-hot MFMA (no sort, no gather); with compute_assign the assignment is computed (and
+// written) in the same pass, otherwise read.  Leaves w.partial / w.wg_counts ready for
+// launch_finalize with max_items = K * (*grid_out) and wg_per_cluster = *grid_out.
+fk_status launch_stream_update(const Geometry& g, const Workspace& w, const void* X,
+                               int32_t* assign, bool compute_assign, int* grid_out,
+                               hipStream_t s);
+bool fused_update_enabled(const Geometry& g);
+void set_fused_update_option(int v);       // 0 = never, otherwise whenever the shape allows
 
 // Comparator: the standard implementation (paper Algorithm 1); see fk_standard.hip.
 fk_status launch_standard_assign(const Geometry& g, const Workspace& w, const void* X,

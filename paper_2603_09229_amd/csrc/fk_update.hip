@@ -154,17 +154,31 @@ __global__ __launch_bounds__(1024) void finalize_kernel(
     uint16_t* __restrict__ C_lp_out, float* __restrict__ C_lp_f32_out,
     uint16_t* __restrict__ c_frag, float* __restrict__ c_bias, int32_t* __restrict__ counts,
     float* __restrict__ sums, int d, int K, int64_t max_items, int ktiles, int dch,
-    int accumulate, int normalise, int bf) {
+    int accumulate, int normalise, int bf, const int32_t* __restrict__ wg_counts, int G) {
     __shared__ float red[4096];
     __shared__ float nrm[512];
+    __shared__ int cred[16];
     const int b = blockIdx.y, k = blockIdx.x, tid = threadIdx.x;
-    seg_off += (size_t)b * (K + 1);
-    item_off += (size_t)b * (K + 1);
     int dpow = 4;
     while (dpow < d) dpow <<= 1;
     const int LR = dpow >> 2;                     // threads per row, 4 features each
     const int slots = (int)blockDim.x / LR, slot = tid / LR, col = (tid % LR) * 4;
-    const int i0 = item_off[k], i1 = item_off[k + 1];
+    int i0, i1;
+    if (wg_counts) {
+        // few-cluster path: cluster k owns G partial rows and G partial counts
+        i0 = k * G;
+        i1 = i0 + G;
+        int v = 0;
+        for (int g = tid; g < G; g += (int)blockDim.x) v += wg_counts[((size_t)b * K + k) * G + g];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+        if ((tid & 63) == 0) cred[tid >> 6] = v;
+    } else {
+        seg_off += (size_t)b * (K + 1);
+        item_off += (size_t)b * (K + 1);
+        i0 = item_off[k];
+        i1 = item_off[k + 1];
+    }
     // read the running count before anyone overwrites it (barrier below)
     const int n_prev = accumulate ? counts[(size_t)b * K + k] : 0;
     const float* P = partial + (size_t)b * max_items * d;
@@ -186,7 +200,12 @@ __global__ __launch_bounds__(1024) void finalize_kernel(
     *(floatx4*)&red[slot * dpow + col] = acc;
     __syncthreads();
     const int T = (int)blockDim.x;
-    const int n = seg_off[k + 1] - seg_off[k] + n_prev;
+    int n = n_prev;
+    if (wg_counts) {
+        for (int q = 0; q < ((int)blockDim.x + 63) / 64; ++q) n += cred[q];
+    } else {
+        n += seg_off[k + 1] - seg_off[k];
+    }
     for (int j = tid; j < d; j += T) {
         float s = 0.f;
         for (int q = 0; q < slots; ++q) s += red[q * dpow + j];   // fixed order
@@ -260,7 +279,8 @@ fk_status launch_segment_reduce(const Geometry& g, const Workspace& w, const voi
 }
 
 fk_status launch_finalize(const Geometry& g, const Workspace& w, const int32_t* seg_off,
-                          const int32_t* item_off, const FinalizeArgs& a, hipStream_t s) {
+                          const int32_t* item_off, const FinalizeArgs& a, hipStream_t s,
+                          const int32_t* wg_counts, int wg_per_cluster) {
     uint16_t* lp16 = g.t == FK_F32 ? nullptr : (uint16_t*)a.C_out_lp;
     float* lp32 = g.t == FK_F32 ? (float*)a.C_out_lp : nullptr;
     if (lp32 == a.C_out_f32) lp32 = nullptr;
@@ -273,7 +293,7 @@ fk_status launch_finalize(const Geometry& g, const Workspace& w, const int32_t* 
     hipLaunchKernelGGL(finalize_kernel, dim3(g.K, g.B), dim3(threads), 0, s, w.partial, seg_off,
                        item_off, a.C_prev_f32, a.C_out_f32, lp16, lp32, frag, a.c_bias, a.counts,
                        a.sums, g.d, g.K, g.max_items, g.ktiles, g.dchunks, a.accumulate ? 1 : 0,
-                       a.normalise ? 1 : 0, g.t == FK_BF16 ? 1 : 0);
+                       a.normalise ? 1 : 0, g.t == FK_BF16 ? 1 : 0, wg_counts, wg_per_cluster);
     FK_HIP(hipGetLastError());
     return FK_OK;
 }

@@ -83,7 +83,13 @@ def test_plan_describes_the_choice_per_shape():
     assert "mfma_stream" in fk.fk_plan(1, 1 << 24, 64, 16, f16)
     assert "mfma_wide(chunks=32" in fk.fk_plan(1, 1 << 20, 512, 65536, f16)
     assert "sort=2pass" in fk.fk_plan(1, 1 << 20, 512, 65536, f16)
+    # few clusters: the sort-free update fused into the assignment pass, unless switched off
+    assert "stream_update" in fk.fk_plan(1, 1 << 24, 64, 16, f16)
+    assert "stream_update" not in fk.fk_plan(1, 1 << 24, 64, 16, torch.float32)
+    assert "stream_update" not in fk.fk_plan(1, 1 << 24, 64, 33, f16)
+    fk.fk_set_option("fused_update", 0)
     assert "workgroup_per_item" in fk.fk_plan(1, 1 << 24, 64, 16, f16)
+    fk.fk_set_option("fused_update", -1)
     assert fk.fk_plan(1, 100, 12, 3, f16) == "unsupported"
     fk.fk_set_option("assign_variant", 1)
     assert "variant=1" in fk.fk_plan(1, 1 << 20, 128, 1024, f16)

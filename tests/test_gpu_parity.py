@@ -389,3 +389,103 @@ def test_iteration_replays_from_a_hip_graph(dtype, N, d, K):
         torch.cuda.synchronize()
         assert torch.equal(C_g, C_e) and torch.equal(a_g, a_e) and torch.equal(n_g, n_e), step
         assert torch.equal(lp_g, lp_e)
+
+
+# ---------------------------------------------------------------------------------------
+# Few clusters (16-bit storage, K <= 32, d <= 128): the sort-free one-hot MFMA update, fused
+# with the assignment inside fk_lloyd_iter.  fk_set_option("fused_update", 0) sends the same
+# shape down the general sort-inverse path, so the two can be compared.
+FEW_CLUSTER_CASES = [
+    # dtype, B, N, d, K, zipf
+    (torch.float16, 1, 100000, 64, 16, 1.2),      # the skewed large-N / small-K recipe, scaled
+    (torch.bfloat16, 3, 5000, 128, 32, 0.0),      # full table, widest row, batched
+    (torch.float16, 1, 4099, 64, 17, 0.0),        # ragged last batch
+    (torch.float16, 2, 1000, 8, 3, 0.0),          # narrowest row: one 16-byte piece per point
+    (torch.bfloat16, 1, 3000, 24, 5, 0.0),        # d = 8 mod 16, no swizzle
+    (torch.float16, 1, 2500, 72, 9, 0.0),         # d not a multiple of 32: half-used column block
+    (torch.float16, 1, 7000, 96, 2, 0.0),
+    (torch.float16, 1, 31, 64, 4, 0.0),           # less than one batch
+    (torch.float16, 1, 1, 16, 1, 0.0),            # one point, one cluster
+    (torch.bfloat16, 1, 33, 32, 32, 0.0),         # K about N: most clusters nearly empty
+]
+
+
+@pytest.fixture
+def general_path_switch():
+    yield lambda on: fk.fk_set_option("fused_update", 0 if on else -1)
+    fk.fk_set_option("fused_update", -1)
+
+
+@pytest.mark.parametrize("dtype,B,N,d,K,zipf", FEW_CLUSTER_CASES)
+def test_few_cluster_iteration_matches_oracle_and_general_path(dtype, B, N, d, K, zipf, general_path_switch):
+    w, X, lab, C0 = _problem(dtype, B, N, d, K, seed=700 + N + K, zipf=zipf)
+    Xd = X.to(DEV)
+    assert "stream_update" in fk.fk_plan(B, N, d, K, dtype)
+    C_f = C0.to(DEV).clone()
+    a_f, n_f, lp_f = fk.fk_lloyd_iter(Xd, C_f, 1)
+    general_path_switch(True)
+    assert "stream_update" not in fk.fk_plan(B, N, d, K, dtype)
+    C_s = C0.to(DEV).clone()
+    a_s, n_s, lp_s = fk.fk_lloyd_iter(Xd, C_s, 1)
+    general_path_switch(False)
+    torch.cuda.synchronize()
+    # same scores, same tie rules: identical assignments and counts; sums differ in order only
+    assert torch.equal(a_f, a_s) and torch.equal(n_f, n_s)
+    consumed = C0.to(dtype)
+    for b in range(B):
+        Xb = parity.widen(X[b])
+        parity.check_assign(Xb, parity.widen(consumed[b]), a_f[b].cpu().numpy())
+        parity.check_update(Xb, a_f[b].cpu().numpy(), C0[b].numpy(), C_f[b].cpu().numpy(),
+                            n_f[b].cpu().numpy(), parity.CENTROID_TOL[dtype])
+        parity.check_centroids(C_f[b].cpu().numpy(), C_s[b].cpu().numpy(), 5e-5, "fused vs sort-inverse")
+    assert torch.equal(lp_f.cpu(), C_f.cpu().to(dtype))
+
+
+@pytest.mark.parametrize("dtype,B,N,d,K,zipf", FEW_CLUSTER_CASES)
+def test_few_cluster_update_alone(dtype, B, N, d, K, zipf, general_path_switch):
+    """fk_update on given assignments: streamed one-hot update against the oracle and against
+    the sort-inverse path; an empty cluster keeps its centroid."""
+    w, X, lab, C0 = _problem(dtype, B, N, d, K, seed=800 + N + K, zipf=zipf)
+    a = lab.clone()
+    if K > 2:
+        a[a == 1] = 0
+    C_f, lp_f, n_f = fk.fk_update(X.to(DEV), a.to(DEV), C0.to(DEV))
+    general_path_switch(True)
+    C_s, lp_s, n_s = fk.fk_update(X.to(DEV), a.to(DEV), C0.to(DEV))
+    general_path_switch(False)
+    torch.cuda.synchronize()
+    assert torch.equal(n_f, n_s)
+    for b in range(B):
+        parity.check_update(parity.widen(X[b]), a[b].numpy(), C0[b].numpy(), C_f[b].cpu().numpy(),
+                            n_f[b].cpu().numpy(), parity.CENTROID_TOL[dtype])
+        parity.check_centroids(C_f[b].cpu().numpy(), C_s[b].cpu().numpy(), 5e-5, "streamed vs sort-inverse")
+    assert torch.equal(lp_f.cpu(), C_f.cpu().to(dtype))
+
+
+def test_few_cluster_path_is_bit_reproducible_and_multi_iteration():
+    w = wl.C4.scaled(N=150001)
+    X, lab = wl.make_points(w, return_labels=True)
+    Xd = X.to(DEV)
+    C0 = wl.gather_rows(X, wl.init_rows(w, lab)).to(DEV)
+    Ca, Cb = C0.clone(), C0.clone()
+    a1, n1, lp1 = fk.fk_lloyd_iter(Xd, Ca, 4)
+    for _ in range(4):
+        a2, n2, lp2 = fk.fk_lloyd_iter(Xd, Cb, 1)
+    assert torch.equal(Ca, Cb) and torch.equal(a1, a2) and torch.equal(n1, n2) and torch.equal(lp1, lp2)
+    assert int(n1.sum()) == w.N
+    # the assignment written by the fused pass is what fk_assign gives for the same centroids
+    Cc = C0.clone()
+    a3, _, lp3 = fk.fk_lloyd_iter(Xd, Cc, 1)
+    assert torch.equal(a3, fk.fk_assign(Xd, C0.to(w.torch_dtype)))
+
+
+def test_few_cluster_update_clamps_ids_like_the_sort_path(general_path_switch):
+    w, X, lab, C0 = _problem(torch.float16, 1, 3000, 64, 8, seed=77)
+    a = lab.clone()
+    a[0, :5] = torch.tensor([-3, 8, 100, -1, 7], dtype=torch.int32)
+    C_f, _, n_f = fk.fk_update(X.to(DEV), a.to(DEV), C0.to(DEV))
+    general_path_switch(True)
+    C_s, _, n_s = fk.fk_update(X.to(DEV), a.to(DEV), C0.to(DEV))
+    general_path_switch(False)
+    assert torch.equal(n_f, n_s)
+    parity.check_centroids(C_f[0].cpu().numpy(), C_s[0].cpu().numpy(), 5e-5, "clamped ids")
