@@ -264,13 +264,21 @@ def compare_standard(torch, fk, wl, dev):
         C = torch.zeros((1, K, d), dtype=torch.float32, device=dev)
         ws = fk.make_workspace(1, N, d, K, torch.float16, dev)
         sums = torch.empty((1, K, d), dtype=torch.float32, device=dev)
+        fk.fk_set_option("fused_update", 0)
         t_si = _time_us(torch, lambda: fk.fk_update(X, lab, C, ws=ws))
+        fk.fk_set_option("fused_update", -1)
         t_at = _time_us(torch, lambda: fk.fk_standard_update(X, lab, C, sums=sums))
         nbytes = N * (d * 2 + 12)
-        out["update"].append({"N": N, "K": K, "d": d, "zipf_s": zipf, "sort_inverse_us": t_si,
-                              "atomic_scatter_us": t_at, "speedup": t_at / t_si,
-                              "sort_inverse_gbps": nbytes / t_si / 1e3,
-                              "atomic_scatter_gbps": N * (d * 2 + 4) / t_at / 1e3})
+        row = {"N": N, "K": K, "d": d, "zipf_s": zipf, "sort_inverse_us": t_si,
+               "atomic_scatter_us": t_at, "speedup": t_at / t_si,
+               "sort_inverse_gbps": nbytes / t_si / 1e3,
+               "atomic_scatter_gbps": N * (d * 2 + 4) / t_at / 1e3}
+        if "stream_update" in fk.fk_plan(1, N, d, K, torch.float16):
+            # few clusters: the sort-free one-hot MFMA update reads X (and the ids) once, streaming
+            t_oh = _time_us(torch, lambda: fk.fk_update(X, lab, C, ws=ws))
+            row.update({"streamed_onehot_us": t_oh, "streamed_onehot_gbps": N * (d * 2 + 4) / t_oh / 1e3,
+                        "speedup_onehot_over_sort_inverse": t_si / t_oh})
+        out["update"].append(row)
         del X, lab
     print(json.dumps(out))
     return 0

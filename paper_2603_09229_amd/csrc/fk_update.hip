@@ -155,8 +155,12 @@ __global__ __launch_bounds__(1024) void finalize_kernel(
     uint16_t* __restrict__ c_frag, float* __restrict__ c_bias, int32_t* __restrict__ counts,
     float* __restrict__ sums, int d, int K, int64_t max_items, int ktiles, int dch,
     int accumulate, int normalise, int bf, const int32_t* __restrict__ wg_counts, int G) {
-    __shared__ float red[4096];
-    __shared__ float nrm[512];
+    // dynamic LDS: 4 floats per thread for the row sums, then d floats for the squared entries
+    // (a fixed worst-case array would cap the small workgroups of many-cluster shapes at a
+    // few per CU)
+    extern __shared__ float fin_lds[];
+    float* red = fin_lds;
+    float* nrm = fin_lds + 4 * blockDim.x;
     __shared__ int cred[16];
     const int b = blockIdx.y, k = blockIdx.x, tid = threadIdx.x;
     int dpow = 4;
@@ -231,15 +235,17 @@ __global__ __launch_bounds__(1024) void finalize_kernel(
     if (tid == 0) counts[(size_t)b * K + k] = n;
     if (normalise && c_frag) {
         __syncthreads();
-        if (tid == 0) {
-            // same association as the stand-alone layout kernel: groups of 8 features first
-            float n2 = 0.f;
-            for (int g0 = 0; g0 < d; g0 += 8) {
-                float ss = 0.f;
-                for (int e = 0; e < 8; ++e) ss = __fadd_rn(ss, nrm[g0 + e]);
-                n2 = __fadd_rn(n2, ss);
+        // same association as the stand-alone layout kernel: groups of 8 features first (one
+        // thread per group; the first wave holds them all, d <= 512), then the groups in order
+        if (tid < 64) {
+            float ss = 0.f;
+            if (tid * 8 < d) {
+                for (int e = 0; e < 8; ++e) ss = __fadd_rn(ss, nrm[tid * 8 + e]);
             }
-            c_bias[((size_t)b * ktiles) * 32 + k] = -0.5f * n2;
+            float n2 = 0.f;
+            for (int g0 = 0; g0 * 8 < d; ++g0)
+                n2 = __fadd_rn(n2, __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(ss), g0)));
+            if (tid == 0) c_bias[((size_t)b * ktiles) * 32 + k] = -0.5f * n2;
         }
     }
 }
@@ -290,7 +296,8 @@ fk_status launch_finalize(const Geometry& g, const Workspace& w, const int32_t* 
     // thread per feature
     int threads = g.max_items / g.K > 64 ? 1024 : 256;
     if (g.max_items / g.K <= 4 && g.d <= 128) threads = g.d <= 64 ? 64 : 128;
-    hipLaunchKernelGGL(finalize_kernel, dim3(g.K, g.B), dim3(threads), 0, s, w.partial, seg_off,
+    const size_t lds = ((size_t)4 * threads + g.d) * sizeof(float);
+    hipLaunchKernelGGL(finalize_kernel, dim3(g.K, g.B), dim3(threads), lds, s, w.partial, seg_off,
                        item_off, a.C_prev_f32, a.C_out_f32, lp16, lp32, frag, a.c_bias, a.counts,
                        a.sums, g.d, g.K, g.max_items, g.ktiles, g.dchunks, a.accumulate ? 1 : 0,
                        a.normalise ? 1 : 0, g.t == FK_BF16 ? 1 : 0, wg_counts, wg_per_cluster);

@@ -85,7 +85,43 @@ def test_c3_full_size_batched():
 
 
 def test_c4_full_size_skewed():
+    """Few clusters: fk_lloyd_iter takes the fused one-hot pass here."""
+    assert "stream_update" in fk.fk_plan(wl.C4.B, wl.C4.N, wl.C4.d, wl.C4.K, wl.C4.torch_dtype)
     _run_incore(wl.C4, n_points=8192, n_clusters=4, instances=[0])
+
+
+def test_c4_full_size_skewed_general_path():
+    """The same shape down the general path (streaming assign, sort-inverse, gather-reduce)."""
+    fk.fk_set_option("fused_update", 0)
+    try:
+        _run_incore(wl.C4, n_points=8192, n_clusters=4, instances=[0])
+    finally:
+        fk.fk_set_option("fused_update", -1)
+
+
+def test_c4_full_size_update_alone_with_the_true_labels():
+    """fk_update on the generating labels (the skew is then exactly the recipe's Zipf law):
+    streamed one-hot update and sort-inverse update agree on the counts exactly and on the
+    centroids to summation order, and sampled clusters match the oracle's means."""
+    w = wl.C4
+    X, lab = wl.make_points(w, device=DEV, return_labels=True)
+    C0 = wl.gather_rows(X, wl.init_rows(w, lab)).contiguous()
+    ws = fk.make_workspace(w.B, w.N, w.d, w.K, w.torch_dtype, DEV)
+    C_f, _, n_f = fk.fk_update(X, lab, C0, ws=ws)
+    fk.fk_set_option("fused_update", 0)
+    try:
+        C_s, _, n_s = fk.fk_update(X, lab, C0, ws=ws)
+    finally:
+        fk.fk_set_option("fused_update", -1)
+    torch.cuda.synchronize()
+    hist = torch.bincount(lab[0].to(torch.int64), minlength=w.K)
+    assert torch.equal(n_f[0].to(torch.int64), hist) and torch.equal(n_f, n_s)
+    parity.check_centroids(C_f[0].cpu().numpy(), C_s[0].cpu().numpy(), 5e-5, "streamed vs sort-inverse")
+    for k in (0, 7, 15):                       # largest, middle and smallest cluster
+        Xm = parity.widen(X[0][lab[0] == k])
+        u = oracle.update(Xm, np.zeros(len(Xm), np.int32), C0[0][k:k + 1].cpu().numpy())
+        parity.check_centroids(C_f[0][k:k + 1].cpu().numpy(), u["C"],
+                               parity.CENTROID_TOL[w.torch_dtype], f"cluster {k}")
 
 
 def test_paper_large_k_d512_shape():
