@@ -261,6 +261,10 @@ int fk_set_option(const char* name, int value) {
         set_assign_variant_override(value);
         return FK_OK;
     }
+    if (name && strcmp(name, "assign_stream") == 0 && value >= -1 && value <= 1) {
+        set_assign_stream_option(value);
+        return FK_OK;
+    }
     if (name && strcmp(name, "fused_update") == 0 && value >= -1 && value <= 1) {
         set_fused_update_option(value);
         return FK_OK;
@@ -280,12 +284,11 @@ int fk_plan(int B, int64_t N, int d, int K, fk_dtype t, char* buf, size_t buf_by
         return FK_EUNSUPPORTED;
     }
     char assign[96];
-    const int st = (16 / g.dchunks) < 8 ? (16 / g.dchunks) : 8;
     if (t == FK_F32)
         snprintf(assign, sizeof(assign), "%s", g.d > 128 ? "f32_wide" : ((int64_t)B * N < (1 << 18) ? "f32_split" : "f32"));
     else if (g.dchunks > 8)
         snprintf(assign, sizeof(assign), "mfma_wide(chunks=%d,points_per_wg=256)", g.dchunks);
-    else if (g.ktiles <= st)
+    else if (assign_uses_stream_kernel(g))
         snprintf(assign, sizeof(assign), "mfma_stream(tiles=%d)", g.ktiles);
     else {
         static const int pts[4] = {256, 512, 512, 128};

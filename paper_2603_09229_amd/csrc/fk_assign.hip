@@ -829,13 +829,26 @@ int choose_assign_variant(int64_t total_points) {
 
 void set_assign_variant_override(int v) { g_variant_override = v; }
 
-// FK_ASSIGN_STREAM=0 keeps small-K shapes on the sweeping kernel (experiments).
-static bool stream_enabled() {
-    static bool on = [] {
-        const char* e = getenv("FK_ASSIGN_STREAM");
-        return !(e && atoi(e) == 0);
-    }();
-    return on;
+// Streaming kernel or sweeping kernel for few centroids?  Measured on MI355X: with X well
+// beyond the last-level cache (256 MiB) the streaming kernel's continuous copies win by
+// ~20% up to two centroid tiles; below that size, and from three tiles on, the sweeping
+// kernel's bulk prologue loads are as fast or faster.  g_stream_option: -1 = that rule,
+// 0 = never, 1 = whenever the centroids fit one LDS stage (FK_ASSIGN_STREAM sets the start
+// value; fk_set_option("assign_stream", v) changes it).
+static int g_stream_option = [] {
+    const char* e = getenv("FK_ASSIGN_STREAM");
+    return e ? atoi(e) : -1;
+}();
+
+void set_assign_stream_option(int v) { g_stream_option = v; }
+
+bool assign_uses_stream_kernel(const Geometry& g) {
+    if (g.t == FK_F32 || g.dchunks > 8) return false;
+    const int st = (16 / g.dchunks) < 8 ? (16 / g.dchunks) : 8;
+    if (g.ktiles > st || g_stream_option == 0) return false;
+    if (g_stream_option > 0) return true;
+    const int64_t x_bytes = (int64_t)g.B * g.N * g.d * 2;
+    return g.ktiles <= 2 && x_bytes >= ((int64_t)384 << 20);
 }
 
 static int device_cu_count() {
@@ -853,7 +866,7 @@ static fk_status launch_mfma(const Geometry& g, const void* X, const void* frag,
                              const float* bias, int32_t* assign, float* min_dist,
                              hipStream_t s) {
     constexpr int ST = (16 / DCH) < 8 ? (16 / DCH) : 8;
-    if (g.ktiles <= ST && stream_enabled()) {
+    if (g.ktiles <= ST && assign_uses_stream_kernel(g)) {
         // persistent waves: as many workgroups as fit the chip, each wave striding over
         // 32-point batches
         constexpr int WAVES = 4;

@@ -98,6 +98,9 @@ fk_status launch_assign(const Geometry& g, const void* X, const void* C_or_frag,
 // Tile shape the sweeping assign kernel would use for this many points (see fk_assign.hip).
 int choose_assign_variant(int64_t total_points);
 void set_assign_variant_override(int v);   // -1 = choose from the shape
+// Few centroids: persistent streaming kernel instead of the sweeping one (see fk_assign.hip).
+bool assign_uses_stream_kernel(const Geometry& g);
+void set_assign_stream_option(int v);      // -1 = by shape, 0 = never, 1 = whenever eligible
 // Stable argsort by cluster id -> sorted_idx, seg_off (+ item_off when w.item_off != NULL).
 fk_status launch_sort_inverse(const Geometry& g, const Workspace& w, const int32_t* assign,
                               int32_t* sorted_idx, int32_t* seg_off, int32_t* item_off,

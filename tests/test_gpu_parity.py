@@ -69,6 +69,30 @@ def test_assign_matches_oracle(dtype, B, N, d, K):
         assert (np.abs(md[b][same] - ref["best"][same]) <= tol[same]).all()
 
 
+@pytest.mark.parametrize("dtype,B,N,d,K", [
+    (torch.float16, 1, 4099, 64, 16), (torch.float16, 1, 3001, 64, 100), (torch.bfloat16, 2, 2500, 128, 64),
+    (torch.float16, 1, 513, 8, 5), (torch.float16, 1, 300, 24, 40), (torch.float16, 1, 5000, 32, 250),
+    (torch.bfloat16, 1, 1000, 96, 33), (torch.float16, 1, 31, 64, 4),
+])
+def test_streaming_and_sweeping_assign_kernels_agree(dtype, B, N, d, K):
+    """Few centroids: the persistent streaming kernel (picked for X beyond the last-level
+    cache) and the sweeping kernel compute the same scores with the same tie rules."""
+    w, X, _, C0 = _problem(dtype, B, N, d, K, seed=400 + N + K)
+    C = C0.to(dtype).to(DEV)
+    try:
+        fk.fk_set_option("assign_stream", 1)
+        assert "mfma_stream" in fk.fk_plan(B, N, d, K, dtype)
+        a1, md1 = fk.fk_assign(X.to(DEV), C, min_dist=True)
+        fk.fk_set_option("assign_stream", 0)
+        assert "mfma_sweep" in fk.fk_plan(B, N, d, K, dtype)
+        a0, md0 = fk.fk_assign(X.to(DEV), C, min_dist=True)
+    finally:
+        fk.fk_set_option("assign_stream", -1)
+    assert torch.equal(a0, a1) and torch.equal(md0, md1)
+    for b in range(B):
+        parity.check_assign(parity.widen(X[b]), parity.widen(C0.to(dtype)[b]), a1[b].cpu().numpy())
+
+
 def test_assign_exact_duplicates_go_to_lowest_index():
     w, X, _, C0 = _problem(torch.float16, 1, 2000, 128, 96, seed=7)
     C = C0.to(torch.float16)
