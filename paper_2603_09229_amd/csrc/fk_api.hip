@@ -76,9 +76,13 @@ bool make_geometry(int B, int64_t N, int d, int K, fk_dtype t, Geometry* g) {
         g->pass_bits[1] = g->sort_bits - g->pass_bits[0];
         nbmax = 1 << g->pass_bits[1];
     }
-    // sort workgroups own whole sub-tiles of 4096 keys; at most 4096 workgroups per instance
+    // sort workgroups own whole sub-tiles of 4096 keys, one each (keys then stay in registers
+    // between the scatter's two passes) until the table of per-workgroup histograms gets too
+    // large: at most 4096 workgroups per instance for the single pass (up to 2048 bins),
+    // 65536 for the two-pass sort (up to 256 bins per pass)
     (void)nbmax;
-    int64_t T = 4096 * cdiv(N, (int64_t)4096 * 4096);
+    const int64_t max_blocks = g->sort_passes == 1 ? 4096 : 65536;
+    int64_t T = 4096 * cdiv(N, (int64_t)4096 * max_blocks);
     g->sort_tile = (int)T;
     g->sort_blocks = (int)cdiv(N, T);
     // rows reduced into one partial row: 256 by one wave, or, for N above 4M points, N/4096 by

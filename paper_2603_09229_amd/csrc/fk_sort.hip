@@ -232,6 +232,62 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_scatter_kernel(
     const uint64_t lt = lanemask_lt();
     // info[j] = rank among equal digits of the batch | (size of that group << 8)
     int info[kBatches];
+
+    if (rounds == 1) {
+        // Keys, ranks and each key's position inside its wave's run of the digit stay in
+        // registers between the two passes.  Pass 1: every lane reads the wave's running count
+        // of its digit, then the first lane of each group of equal digits adds the group's
+        // size; LDS executes a wave's operations in order, so the eight batches need no wait
+        // between them.
+        int pre[kBatches];
+#pragma unroll
+        for (int j = 0; j < kBatches; ++j) {
+            const bool valid = k[j] >= 0;
+            const int digit = valid ? (k[j] >> shift) & mask : 0;
+            const uint64_t peers = match_digit(digit, nbits, __ballot(valid));
+            const int rank = __popcll(peers & lt), cnt = __popcll(peers);
+            info[j] = rank;
+            pre[j] = valid ? mine[digit] : 0;
+            __builtin_amdgcn_wave_barrier();
+            if (valid && rank == 0) atomicAdd(&mine[digit], cnt);
+            __builtin_amdgcn_wave_barrier();
+        }
+        __syncthreads();
+        // counts -> start positions: global bin offset + earlier workgroups + earlier waves
+        for (int i = tid; i < NB; i += kSortThreads) {
+            int run = off[i] + H[(size_t)i * nb];
+            for (int w = 0; w < kSortWaves; ++w) {
+                const int t = wcnt[w * NB + i];
+                wcnt[w * NB + i] = run;
+                run += t;
+            }
+        }
+        __syncthreads();
+        // pass 2: position = start of the wave's run + position inside the run
+        int v[kBatches];
+        if (vals_in) {
+#pragma unroll
+            for (int j = 0; j < kBatches; ++j) {
+                const int64_t i = base0 + j * 64 + lane;
+                v[j] = i < N ? vals_in[i] : 0;
+            }
+        }
+        int start[kBatches];
+#pragma unroll
+        for (int j = 0; j < kBatches; ++j) start[j] = k[j] >= 0 ? mine[(k[j] >> shift) & mask] : 0;
+#pragma unroll
+        for (int j = 0; j < kBatches; ++j) {
+            if (k[j] >= 0) {
+                const int pos = start[j] + pre[j] + info[j];
+                vals_out[pos] = vals_in ? v[j] : (int32_t)(base0 + j * 64 + lane);
+                if (keys_out) keys_out[pos] = k[j];
+            }
+        }
+        return;
+    }
+
+    // More than one round per workgroup (beyond 16M keys per instance): ranks are recomputed
+    // in the second pass and the wave's cursors advance batch by batch.
     auto rank_round = [&](bool count) {
 #pragma unroll
         for (int j = 0; j < kBatches; ++j) {
@@ -267,10 +323,8 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_scatter_kernel(
     for (int r = 0; r < rounds; ++r) {
         const int64_t base = base0 + (int64_t)r * kSubTile;
         if (base >= N) break;
-        if (rounds > 1) {                       // single round: keys and ranks are still here
-            load_round(keys, base, N, lane, kmax, k);
-            rank_round(false);
-        }
+        load_round(keys, base, N, lane, kmax, k);
+        rank_round(false);
         int v[kBatches];
         if (vals_in) {
 #pragma unroll
