@@ -171,9 +171,17 @@ fk_status fk_standard_update(const void* X, const int32_t* assign, const float* 
  * tuning run).  fk_plan writes a one-line description of what the in-core entry points would
  * launch for this shape into buf (host memory, NUL-terminated, truncated to buf_bytes):
  * assign kernel and tile shape, sort passes and tiling, reduction granularity, workspace.
- * Host-only.  fk_set_option("assign_variant", v) forces tile shape v in 0..3 of the sweeping
- * assign kernel for every later call of this process (-1 = back to the heuristic); it exists
- * so that the heuristic can be checked against an exhaustive sweep.
+ * Host-only.  fk_set_option changes a choice for every later call of this process, so that the
+ * choices can be checked against the alternatives (value -1 = back to the rule of the shape):
+ *   "assign_variant" v   tile shape v in 0..3 of the sweeping assign kernel
+ *   "assign_stream"  0/1 few centroids: never / always (when they fit one LDS stage) take the
+ *                        persistent streaming assign kernel
+ *   "fused_update"   0   few clusters: do not take the sort-free update below
+ * Few clusters (FK_F16 / FK_BF16, K <= 32, d <= 128): fk_lloyd_iter computes assignment and
+ * per-workgroup tables of sums in ONE pass over X (a one-hot MFMA adds each 32-point batch into
+ * the K x d table; Section 4.2's on-chip partial sums with no sort needed), and fk_update
+ * streams X once in storage order instead of sorting and gathering.  Same results as the
+ * general path up to fp32 summation order; still no floating-point atomics, bit-reproducible.
  */
 int fk_plan(int B, int64_t N, int d, int K, fk_dtype t, char* buf, size_t buf_bytes);
 int fk_set_option(const char* name, int value);
