@@ -9,6 +9,8 @@
 // monotone in address.
 //
 // Only integer LDS counters are used; no floating-point data is touched here.
+#include <stdlib.h>
+
 #include "fk_common.h"
 
 namespace fk {
@@ -188,12 +190,16 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_scatter_kernel(
     const int32_t* __restrict__ H, const int32_t* __restrict__ tot,
     int32_t* __restrict__ vals_out, int32_t* __restrict__ keys_out,
     int32_t* __restrict__ seg_off, int32_t* __restrict__ item_off, int64_t N, int rounds,
-    int NB, int shift, int mask, int kmax, int nbits, int R) {
+    int NB, int shift, int mask, int kmax, int nbits, int R, int staged) {
     constexpr int kSortThreads = kSortWaves * 64, kBatches = kSubTile / kSortThreads;
     extern __shared__ int lds[];
     int* off = lds;                    // [NB]
     int* scratch = off + NB;           // [40]
     int* wcnt = scratch + 40;          // [kSortWaves][NB]
+    // staged only: [NB] bin starts, then the tile's keys and values in sorted order
+    int* gdel = wcnt + kSortWaves * NB;
+    int* skey = gdel + NB;
+    int* sval = skey + kSubTile;
     const int b = blockIdx.y, blk = blockIdx.x, nb = gridDim.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     keys += (size_t)b * N;
@@ -253,6 +259,53 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_scatter_kernel(
             __builtin_amdgcn_wave_barrier();
         }
         __syncthreads();
+        int v[kBatches];
+        if (vals_in) {
+#pragma unroll
+            for (int j = 0; j < kBatches; ++j) {
+                const int64_t i = base0 + j * 64 + lane;
+                v[j] = i < N ? vals_in[i] : 0;
+            }
+        }
+        if (staged) {
+            // Few bins, long runs: the tile is first put in sorted order in LDS and then
+            // written by consecutive threads, so that a store instruction covers a few
+            // contiguous runs instead of 64 scattered words.
+            for (int i = tid; i < NB; i += kSortThreads) {
+                int run = 0;
+                for (int w = 0; w < kSortWaves; ++w) {
+                    const int t = wcnt[w * NB + i];
+                    wcnt[w * NB + i] = run;           // where wave w's run starts inside the bin's
+                    run += t;
+                }
+                gdel[i] = run;                        // the tile's count of bin i
+            }
+            __syncthreads();
+            block_exclusive_scan(gdel, NB, scratch);  // -> where bin i starts inside the tile
+#pragma unroll
+            for (int j = 0; j < kBatches; ++j) {
+                if (k[j] >= 0) {
+                    const int digit = (k[j] >> shift) & mask;
+                    const int lp = gdel[digit] + mine[digit] + pre[j] + info[j];
+                    skey[lp] = k[j];
+                    sval[lp] = vals_in ? v[j] : (int32_t)(base0 + j * 64 + lane);
+                }
+            }
+            __syncthreads();
+            // global position = position in the tile + (global start of the tile's run of the bin
+            // - its start inside the tile)
+            for (int i = tid; i < NB; i += kSortThreads) gdel[i] = off[i] + H[(size_t)i * nb] - gdel[i];
+            __syncthreads();
+            const int64_t tile0 = (int64_t)blk * kSubTile;
+            const int live = (int)min((int64_t)kSubTile, N - tile0);
+            for (int i = tid; i < live; i += kSortThreads) {
+                const int key = skey[i];
+                const int pos = i + gdel[(key >> shift) & mask];
+                vals_out[pos] = sval[i];
+                if (keys_out) keys_out[pos] = key;
+            }
+            return;
+        }
         // counts -> start positions: global bin offset + earlier workgroups + earlier waves
         for (int i = tid; i < NB; i += kSortThreads) {
             int run = off[i] + H[(size_t)i * nb];
@@ -264,14 +317,6 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_scatter_kernel(
         }
         __syncthreads();
         // pass 2: position = start of the wave's run + position inside the run
-        int v[kBatches];
-        if (vals_in) {
-#pragma unroll
-            for (int j = 0; j < kBatches; ++j) {
-                const int64_t i = base0 + j * 64 + lane;
-                v[j] = i < N ? vals_in[i] : 0;
-            }
-        }
         int start[kBatches];
 #pragma unroll
         for (int j = 0; j < kBatches; ++j) start[j] = k[j] >= 0 ? mine[(k[j] >> shift) & mask] : 0;
@@ -424,15 +469,32 @@ static fk_status sort_pass(const Geometry& g, const Workspace& w, const int32_t*
                            s, H, tot, g.sort_blocks, NB);
     FK_HIP(hipGetLastError());
     const int waves = wide ? 4 : 8;
-    const size_t lds = (size_t)(NB + 40 + waves * NB) * sizeof(int);
+    // One tile per workgroup: sorted in LDS first, then written in contiguous runs.  Measured
+    // (2^20 .. 2^25 keys): pays from 32 bins (below that a wave's stores already fall into few
+    // runs) up to 1024 (beyond, the LDS footprint costs more than the runs, 1-2 keys, give);
+    // 2x on the 64..256-bin passes of the two-pass sort.  FK_SORT_STAGE_BINS moves the upper limit.
+    static const int stage_max_bins = [] {
+        const char* e = getenv("FK_SORT_STAGE_BINS");
+        return e ? atoi(e) : 1024;
+    }();
+    const int staged = rounds == 1 && NB >= 32 && NB <= stage_max_bins ? 1 : 0;
+    const size_t lds = (size_t)(NB + 40 + waves * NB + (staged ? NB + 2 * kSubTile : 0)) * sizeof(int);
+    if (lds > 64 * 1024) {
+        static bool attr_set[2] = {false, false};
+        if (!attr_set[wide]) {
+            FK_HIP(hipFuncSetAttribute(wide ? (const void*)sort_scatter_kernel<4> : (const void*)sort_scatter_kernel<8>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
+            attr_set[wide] = true;
+        }
+    }
     if (wide)
         hipLaunchKernelGGL(sort_scatter_kernel<4>, grid, dim3(256), lds, s, keys, vals_in, H, tot,
                            vals_out, keys_out, seg_off, item_off, g.N, rounds, NB, shift, mask,
-                           g.K - 1, nbits, g.rows_per_item);
+                           g.K - 1, nbits, g.rows_per_item, staged);
     else
         hipLaunchKernelGGL(sort_scatter_kernel<8>, grid, dim3(512), lds, s, keys, vals_in, H, tot,
                            vals_out, keys_out, seg_off, item_off, g.N, rounds, NB, shift, mask,
-                           g.K - 1, nbits, g.rows_per_item);
+                           g.K - 1, nbits, g.rows_per_item, staged);
     FK_HIP(hipGetLastError());
     return FK_OK;
 }

@@ -115,7 +115,9 @@ def test_assign_does_not_depend_on_tiling_position():
 
 
 SORT_CASES = [(1, 5000, 1), (2, 4097, 16), (1, 100000, 1000), (1, 33333, 2048), (1, 70001, 2049),
-              (2, 50000, 5000), (1, 200000, 65536), (1, 1, 5), (1, 300000, 16)]
+              (2, 50000, 5000), (1, 200000, 65536), (1, 1, 5), (1, 300000, 16),
+              # around the limits of the LDS-staged scatter (32 .. 1024 bins), short last tile
+              (3, 9000, 32), (1, 9000, 31), (1, 100, 1024), (1, 50000, 1025), (1, 4096, 700)]
 
 
 @pytest.mark.parametrize("B,N,K", SORT_CASES)
