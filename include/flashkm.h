@@ -27,7 +27,7 @@
  *     enqueue work on it and return without waiting, except fk_lloyd_ooc.  The in-core calls
  *     enqueue kernels only (no memset, no allocation), so after one eager call for a shape
  *     they can be recorded into a HIP graph by stream capture and replayed.
- *   - Supported shapes: 1 <= K <= 65536, 1 <= N, B*N < 2^31, B >= 1,
+ *   - Supported shapes: 1 <= K <= 65536, 1 <= N, B*N < 2^31, 1 <= B <= 65535,
  *     d a multiple of 8 with 8 <= d <= 512.  Anything else returns FK_EUNSUPPORTED or
  *     FK_EINVAL; there is no fallback path.
  *   - Every function returns an fk_status; on failure fk_last_error() holds a message for

@@ -59,6 +59,7 @@ bool make_geometry(int B, int64_t N, int d, int K, fk_dtype t, Geometry* g) {
     if (B < 1 || N < 1 || K < 1 || K > 65536 || d < 8 || d > 512 || (d % 8) != 0) return false;
     if (t != FK_F32 && t != FK_F16 && t != FK_BF16) return false;
     if ((int64_t)B * N >= ((int64_t)1 << 31)) return false;
+    if (B > 65535) return false;                 // instances are the y dimension of every launch
     g->B = B; g->N = N; g->d = d; g->K = K; g->t = t;
     g->dchunks = d <= 32 ? 2 : (d <= 64 ? 4 : (d <= 128 ? 8 : (d <= 256 ? 16 : 32)));
     g->ktiles = (int)cdiv(K, 32);
@@ -164,7 +165,7 @@ static fk_status check_common(const char* fn, int B, int64_t N, int d, int K, fk
         return FK_EINVAL;
     }
     if (!make_geometry(B, N, d, K, t, g)) {
-        set_error("%s: unsupported shape B=%d N=%lld d=%d K=%d (need d%%8==0, 8<=d<=512, K<=65536, B*N<2^31)",
+        set_error("%s: unsupported shape B=%d N=%lld d=%d K=%d (need d%%8==0, 8<=d<=512, K<=65536, B<=65535, B*N<2^31)",
                   fn, B, (long long)N, d, K);
         return FK_EUNSUPPORTED;
     }

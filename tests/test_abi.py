@@ -36,7 +36,7 @@ def test_workspace_sizes_are_sane():
     assert fk.fk_workspace_bytes(1, 1 << 20, 128, 65536, f16) > base
     assert fk.fk_workspace_bytes(1, 1000, 64, 10, f32) % 256 == 0
     for bad in [(0, 10, 64, 4), (1, 0, 64, 4), (1, 10, 12, 4), (1, 10, 520, 4), (1, 10, 64, 0),
-                (1, 10, 64, 65537), (3, 1 << 30, 64, 4)]:
+                (1, 10, 64, 65537), (3, 1 << 30, 64, 4), (65536, 4, 64, 4)]:
         assert fk.fk_workspace_bytes(*bad, f16) == 0
     assert fk.fk_ooc_workspace_bytes(1 << 16, 128, 65536, f16) > 2 * (1 << 16) * 256
     assert fk.fk_ooc_workspace_bytes(0, 128, 16, f16) == 0
