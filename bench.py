@@ -376,6 +376,7 @@ def bench_ooc(args, w, steps, torch, fk, wl, dev):
     print(f"generated in {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
     idx = torch.randint(0, w.N, (w.K,), generator=torch.Generator().manual_seed(w.seed + 1000))
     C = Xh[0][idx].to(torch.float32).to(dev).contiguous()
+    C0 = C.clone()
     chunk = min(1 << 24, w.N)
     need = fk.fk_ooc_workspace_bytes(chunk, w.d, w.K, w.torch_dtype)
     assert 0 < need <= cap - (1 << 30), need
@@ -404,6 +405,9 @@ def bench_ooc(args, w, steps, torch, fk, wl, dev):
                         "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
                         "frac": tf / PEAK_MFMA_F16_TFLOPS, "traffic": None,
                         "note": "whole iteration including the PCIe stream, not the kernel alone"}}
+    if not args.no_cpu_baseline:
+        # sampled: the oracle cannot redo this size; its rate on the sample is scaled up
+        out["cpu_baseline"] = cpu_baseline(w, Xh, C0[None], torch)
     print(json.dumps(out))
     return 0
 
