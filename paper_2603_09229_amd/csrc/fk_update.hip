@@ -295,7 +295,7 @@ fk_status launch_finalize(const Geometry& g, const Workspace& w, const int32_t* 
     // ... and many clusters with one or two rows each: the smallest workgroup that still has a
     // thread per feature
     int threads = g.max_items / g.K > 64 ? 1024 : 256;
-    if (g.max_items / g.K <= 4 && g.d <= 128) threads = g.d <= 64 ? 64 : 128;
+    if (g.max_items / g.K <= 4 && g.d <= 128) threads = 64;
     const size_t lds = ((size_t)4 * threads + g.d) * sizeof(float);
     hipLaunchKernelGGL(finalize_kernel, dim3(g.K, g.B), dim3(threads), lds, s, w.partial, seg_off,
                        item_off, a.C_prev_f32, a.C_out_f32, lp16, lp32, frag, a.c_bias, a.counts,
