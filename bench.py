@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the Lloyd k-means hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c4|c5|p512]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c1|c3|c4|c5|p512|p8m|pk8k]
 
 A step is one full Lloyd iteration (fused assign, sort-inverse, segment reduction,
 merge/normalise) over a synthetic Gaussian mixture already resident in HBM.  The default
@@ -74,7 +74,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     dev = torch.device("cuda:0")
-    short = {"c1": wl.C1, "c2": wl.C2, "c3": wl.C3, "c4": wl.C4, "c5": wl.C5, "p512": wl.P512}
+    short = {"c1": wl.C1, "c2": wl.C2, "c3": wl.C3, "c4": wl.C4, "c5": wl.C5, "p512": wl.P512,
+             "p8m": wl.P8M, "pk8k": wl.PK8K}
     if args.workload not in short:
         print(f"unknown workload {args.workload}", file=sys.stderr)
         return 2

@@ -53,7 +53,11 @@ C5 = Workload("c5_ooc_fp16", 1, 1 << 28, 128, 65536, "fp16", 4.0, 1.0, 0.0, 5, 1
 # D = 512); not one of the five benchmark configurations, used to exercise the wide-feature
 # kernels at scale.
 P512 = Workload("paper_large_k_d512_fp16", 1, 1 << 20, 512, 65536, "fp16", 4.0, 1.0, 0.0, 3, 1006)
-CONFIGS = {w.name: w for w in (C1, C2, C3, C4, C5, P512)}
+# The paper's large-N / small-K end-to-end shape (N = 8M, K = 1024; d = 128 assumed as in its
+# kernel-level experiments) and the shape of its assignment-kernel comparison (N = 1M, K = 8192).
+P8M = Workload("paper_large_n_k1024_fp16", 1, 1 << 23, 128, 1024, "fp16", 4.0, 1.0, 0.0, 5, 1007)
+PK8K = Workload("paper_k8192_fp16", 1, 1 << 20, 128, 8192, "fp16", 4.0, 1.0, 0.0, 5, 1008)
+CONFIGS = {w.name: w for w in (C1, C2, C3, C4, C5, P512, P8M, PK8K)}
 
 
 def _gen(seed: int, device) -> torch.Generator:
