@@ -152,6 +152,16 @@ static size_t sort_workspace_bytes(const Geometry& g) {
     return off;
 }
 
+int device_cu_count() {
+    static int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 256;
+        return n > 0 ? n : 256;
+    }();
+    return cus;
+}
+
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 static fk_status check_common(const char* fn, int B, int64_t N, int d, int K, fk_dtype t,

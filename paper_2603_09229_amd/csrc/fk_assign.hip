@@ -15,28 +15,9 @@
 #include <algorithm>
 
 #include "fk_common.h"
+#include "fk_device.h"
 
 namespace fk {
-
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ float lp_to_float(uint16_t v, bool bf) {
-    return bf ? __uint_as_float((uint32_t)v << 16) : (float)__builtin_bit_cast(_Float16, v);
-}
-
-// round-to-nearest-even from fp32 (finite input)
-__device__ __forceinline__ uint16_t float_to_lp(float f, bool bf) {
-    if (bf) {
-        uint32_t u = __float_as_uint(f);
-        u += 0x7FFFu + ((u >> 16) & 1u);
-        return (uint16_t)(u >> 16);
-    }
-    return __builtin_bit_cast(uint16_t, (_Float16)f);
-}
 
 // ------------------------------------------------------------------------------------
 // Centroid layout kernel.  One workgroup per centroid tile (32 rows).  Thread g < 64*DCH
@@ -47,8 +28,6 @@ __device__ __forceinline__ uint16_t float_to_lp(float f, bool bf) {
 // ROUNDED values, i.e. from exactly what the MFMA multiplies.  Rows >= K get a huge negative
 // finite bias: it must survive having its low mantissa bits overwritten (-inf would turn
 // into a NaN pattern) and still lose against every real score.
-constexpr float kPadBias = -3.0e38f;
-
 template <bool SRC_F32>
 __global__ __launch_bounds__(512) void centroid_layout_kernel(
     const void* __restrict__ src, uint16_t* __restrict__ C_lp, uint16_t* __restrict__ c_frag,
@@ -134,16 +113,6 @@ fk_status launch_round_centroids(const Geometry& g, const float* C_f32, void* C_
 }
 
 // ------------------------------------------------------------------------------------
-template <bool BF>
-__device__ __forceinline__ floatx16 mfma32(uintx4 a, uintx4 b, floatx16 c) {
-    if constexpr (BF)
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    else
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a),
-                                                      __builtin_bit_cast(half8, b), c, 0, 0, 0);
-}
-
 // Direct global -> LDS copy of 16 bytes per lane: the wave's 64 lanes fill 1 KiB starting
 // at the (wave-uniform) LDS address `lds_base`, lane i at lds_base + 16*i.
 __device__ __forceinline__ void copy16_to_lds(const uintx4* gsrc, uintx4* lds_base) {
@@ -804,8 +773,6 @@ static int g_variant_override = [] {
     return e ? atoi(e) : -1;
 }();
 
-static int device_cu_count();
-
 // Workgroups run in rounds of (CUs x workgroups per CU).  A variant is scored by how full its
 // rounds are, (W/S) / ceil(W/S) with W workgroups over S slots, times its steady-state
 // efficiency relative to the 512-point shape (bigger workgroups re-use each centroid tile
@@ -849,16 +816,6 @@ bool assign_uses_stream_kernel(const Geometry& g) {
     if (g_stream_option > 0) return true;
     const int64_t x_bytes = (int64_t)g.B * g.N * g.d * 2;
     return g.ktiles <= 2 && x_bytes >= ((int64_t)384 << 20);
-}
-
-static int device_cu_count() {
-    static int cus = [] {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return 256;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 256;
-        return n > 0 ? n : 256;
-    }();
-    return cus;
 }
 
 template <bool BF, int DCH>

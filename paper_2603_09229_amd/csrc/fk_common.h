@@ -31,6 +31,8 @@ constexpr int kWave = 64;
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t elem_size(fk_dtype t) { return t == FK_F32 ? 4 : 2; }
+// Compute units of the current device (queried once; 256 if the query fails or no GPU is there).
+int device_cu_count();
 
 // ---------------------------------------------------------------- problem geometry
 //

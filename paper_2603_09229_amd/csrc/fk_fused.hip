@@ -17,33 +17,9 @@
 #include <algorithm>
 
 #include "fk_common.h"
+#include "fk_device.h"
 
 namespace fk {
-
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
-typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
-
-namespace {
-
-template <bool BF>
-__device__ __forceinline__ floatx16 mfma32(uintx4 a, uintx4 b, floatx16 c) {
-    if constexpr (BF)
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    else
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a),
-                                                      __builtin_bit_cast(half8, b), c, 0, 0, 0);
-}
-
-__device__ __forceinline__ uint32_t lds_addr(const void* p) {
-    return (uint32_t)(uintptr_t)((__attribute__((address_space(3))) const void*)p);
-}
-
-}  // namespace
 
 // BF: bf16 (else fp16).  DCH: feature chunks of 16 per point (2, 4 or 8).  ASSIGN: compute
 // the assignment here (argmax of x.c_k - ||c_k||^2/2 over the single centroid tile, same
@@ -287,16 +263,6 @@ void set_fused_update_option(int v) { g_fused_option = v; }
 
 bool fused_update_enabled(const Geometry& g) { return g.fused_grid_cap > 0 && g_fused_option != 0; }
 
-static int cu_count() {
-    static int cus = [] {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return 256;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 256;
-        return n > 0 ? n : 256;
-    }();
-    return cus;
-}
-
 template <bool BF, int DCH, bool ASSIGN>
 static fk_status launch_stream_update_t(const Geometry& g, const Workspace& w, const void* X,
                                         int32_t* assign, int* grid_out, hipStream_t s) {
@@ -313,7 +279,7 @@ static fk_status launch_stream_update_t(const Geometry& g, const Workspace& w, c
         per_cu = q;
     }
     const int64_t nbatches = cdiv(g.N, 32);
-    int64_t G = cdiv((int64_t)cu_count() * per_cu, g.B);
+    int64_t G = cdiv((int64_t)device_cu_count() * per_cu, g.B);
     G = std::min<int64_t>(G, g.fused_grid_cap);
     G = std::min<int64_t>(G, cdiv(nbatches, WAVES));
     G = std::max<int64_t>(G, 1);

@@ -9,32 +9,9 @@
 // LDS staging and tile shape as the fused kernel, with the argmin epilogue replaced by
 // stores of ||x||^2 - 2(x.c - ||c||^2/2).  16-bit storage types, d <= 128.
 #include "fk_common.h"
+#include "fk_device.h"
 
 namespace fk {
-
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
-
-namespace {
-
-__device__ __forceinline__ float lp_to_float(uint16_t v, bool bf) {
-    return bf ? __uint_as_float((uint32_t)v << 16) : (float)__builtin_bit_cast(_Float16, v);
-}
-
-template <bool BF>
-__device__ __forceinline__ floatx16 mfma32(uintx4 a, uintx4 b, floatx16 c) {
-    if constexpr (BF)
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    else
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8, a),
-                                                      __builtin_bit_cast(half8, b), c, 0, 0, 0);
-}
-
-}  // namespace
 
 // Kernel 1 of Algorithm 1: D[i][k] = ||x_i||^2 + ||c_k||^2 - 2 x_i.c_k, written to HBM.
 // 8 waves x 64 points per workgroup; centroid tiles staged through LDS (16 KiB stages).

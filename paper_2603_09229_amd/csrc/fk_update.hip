@@ -10,25 +10,11 @@
 // atomics at all and is bit-reproducible.  X is gathered by whole rows through sorted_idx
 // and never permuted in memory.
 #include "fk_common.h"
+#include "fk_device.h"
 
 namespace fk {
 
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
-
 namespace {
-
-__device__ __forceinline__ float lp_to_float(uint16_t v, bool bf) {
-    return bf ? __uint_as_float((uint32_t)v << 16) : (float)__builtin_bit_cast(_Float16, v);
-}
-__device__ __forceinline__ uint16_t float_to_lp(float f, bool bf) {
-    if (bf) {
-        uint32_t u = __float_as_uint(f);
-        u += 0x7FFFu + ((u >> 16) & 1u);
-        return (uint16_t)(u >> 16);
-    }
-    return __builtin_bit_cast(uint16_t, (_Float16)f);
-}
 
 // Largest k in [0,K) with item_off[k] <= item, found by the whole wave 64 probes at a
 // time.  Requires item < item_off[K]; the cluster found is then non-empty.
