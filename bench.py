@@ -54,6 +54,10 @@ def main() -> int:
     ap.add_argument("--compare-standard", action="store_true",
                     help="time the fused assign and the sort-inverse update against the standard "
                          "implementation (materialised distances, atomic scatter) on a few shapes")
+    ap.add_argument("--sweep-choices", action="store_true",
+                    help="time both sides of the host's other kernel choices over a grid of shapes: "
+                         "streaming vs sweeping assign kernel for few centroids, LDS-staged vs "
+                         "direct scatter in the counting sort (prints one JSON line)")
     ap.add_argument("--general-update", action="store_true",
                     help="few-cluster shapes: use the general assign + sort-inverse path instead "
                          "of the fused one-hot pass (for comparing the two)")
@@ -83,6 +87,8 @@ def main() -> int:
         return sweep_variants(torch, fk, dev)
     if args.compare_standard:
         return compare_standard(torch, fk, wl, dev)
+    if args.sweep_choices:
+        return sweep_choices(torch, fk, dev)
     if args.general_update:
         fk.fk_set_option("fused_update", 0)
     w = short[args.workload]
@@ -281,6 +287,42 @@ def compare_standard(torch, fk, wl, dev):
                         "speedup_onehot_over_sort_inverse": t_si / t_oh})
         out["update"].append(row)
         del X, lab
+    print(json.dumps(out))
+    return 0
+
+
+def sweep_choices(torch, fk, dev):
+    """Both sides of two host-side choices, with the side the shape rule picks."""
+    out = {"metric": "kernel_choice_rules", "assign_small_k": [], "sort_scatter": []}
+    f16 = torch.float16
+    for (N, d) in ((1 << 24, 64), (1 << 22, 64), (1 << 20, 64), (1 << 22, 128), (1 << 20, 128), (1 << 22, 32)):
+        X = (torch.randn(1, N, d, device=dev) * 4).half()
+        for K in (16, 64, 128, 256):
+            if K > 32 * (16 // max(2, d // 16)):
+                continue                                   # C no longer fits one LDS stage
+            C = (torch.randn(1, K, d, device=dev) * 4).half()
+            ws = fk.make_workspace(1, N, d, K, f16, dev)
+            a = torch.empty((1, N), dtype=torch.int32, device=dev)
+            us = {}
+            for name, v in (("sweep", 0), ("stream", 1), ("rule", -1)):
+                fk.fk_set_option("assign_stream", v)
+                us[name] = round(_time_us(torch, lambda: fk.fk_assign(X, C, ws=ws, out=a)), 1)
+            fk.fk_set_option("assign_stream", -1)
+            plan = fk.fk_plan(1, N, d, K, f16)
+            out["assign_small_k"].append({"N": N, "d": d, "K": K, "us": us,
+                                          "rule_picks": "stream" if "mfma_stream" in plan else "sweep"})
+        del X
+    for (B, N, K) in ((1, 1 << 20, 256), (1, 1 << 20, 1024), (1, 1 << 20, 2048), (32, 32768, 256), (1, 1 << 24, 16),
+                      (1, 1 << 24, 64), (1, 1 << 24, 1024), (1, 1 << 22, 2048), (1, 1 << 24, 65536), (1, 1 << 25, 4096)):
+        a = torch.randint(0, K, (B, N), dtype=torch.int32, device=dev)
+        ws = torch.empty(fk.fk_workspace_bytes(B, N, 8, K, torch.float32), dtype=torch.uint8, device=dev)
+        us = {}
+        for name, v in (("direct", 0), ("staged_up_to_2048_bins", 2048), ("rule", -1)):
+            fk.fk_set_option("sort_stage_bins", v)
+            us[name] = round(_time_us(torch, lambda: fk.fk_sort_inverse(a, K, ws=ws)), 1)
+        fk.fk_set_option("sort_stage_bins", -1)
+        out["sort_scatter"].append({"B": B, "N": N, "K": K, "us": us})
+        del a, ws
     print(json.dumps(out))
     return 0
 

@@ -176,6 +176,8 @@ fk_status fk_standard_update(const void* X, const int32_t* assign, const float* 
  *   "assign_variant" v   tile shape v in 0..3 of the sweeping assign kernel
  *   "assign_stream"  0/1 few centroids: never / always (when they fit one LDS stage) take the
  *                        persistent streaming assign kernel
+ *   "sort_stage_bins" n  the counting sort's scatter orders its tile in LDS before writing
+ *                        when a pass has 32..n bins (default 1024; 0 = never)
  *   "fused_update"   0   few clusters: do not take the sort-free update below
  * Few clusters (FK_F16 / FK_BF16, K <= 32, d <= 128): fk_lloyd_iter computes assignment and
  * per-workgroup tables of sums in ONE pass over X (a one-hot MFMA adds each 32-point batch into

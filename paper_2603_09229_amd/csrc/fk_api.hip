@@ -280,6 +280,10 @@ int fk_set_option(const char* name, int value) {
         set_assign_stream_option(value);
         return FK_OK;
     }
+    if (name && strcmp(name, "sort_stage_bins") == 0 && value >= -1 && value <= 2048) {
+        set_sort_stage_bins(value);
+        return FK_OK;
+    }
     if (name && strcmp(name, "fused_update") == 0 && value >= -1 && value <= 1) {
         set_fused_update_option(value);
         return FK_OK;

@@ -107,6 +107,8 @@ void set_assign_stream_option(int v);      // -1 = by shape, 0 = never, 1 = when
 fk_status launch_sort_inverse(const Geometry& g, const Workspace& w, const int32_t* assign,
                               int32_t* sorted_idx, int32_t* seg_off, int32_t* item_off,
                               hipStream_t s);
+// Largest bin count for which the scatter stages its tile through LDS (-1 = the built-in 1024).
+void set_sort_stage_bins(int v);
 // Per-item segment sums of gathered rows -> w.partial.
 fk_status launch_segment_reduce(const Geometry& g, const Workspace& w, const void* X,
                                 const int32_t* sorted_idx, const int32_t* seg_off,

@@ -443,6 +443,11 @@ static int ceil_log2(int v) {
     return b;
 }
 
+// upper limit of the LDS-staged scatter, in bins (fk_set_option("sort_stage_bins"); 0 = never)
+static int g_stage_max_bins = 1024;
+
+void set_sort_stage_bins(int v) { g_stage_max_bins = v < 0 ? 1024 : v; }
+
 static fk_status sort_pass(const Geometry& g, const Workspace& w, const int32_t* keys,
                            const int32_t* vals_in, int32_t* vals_out, int32_t* keys_out,
                            int32_t* seg_off, int32_t* item_off, int NB, int shift, int mask,
@@ -472,12 +477,8 @@ static fk_status sort_pass(const Geometry& g, const Workspace& w, const int32_t*
     // One tile per workgroup: sorted in LDS first, then written in contiguous runs.  Measured
     // (2^20 .. 2^25 keys): pays from 32 bins (below that a wave's stores already fall into few
     // runs) up to 1024 (beyond, the LDS footprint costs more than the runs, 1-2 keys, give);
-    // 2x on the 64..256-bin passes of the two-pass sort.  FK_SORT_STAGE_BINS moves the upper limit.
-    static const int stage_max_bins = [] {
-        const char* e = getenv("FK_SORT_STAGE_BINS");
-        return e ? atoi(e) : 1024;
-    }();
-    const int staged = rounds == 1 && NB >= 32 && NB <= stage_max_bins ? 1 : 0;
+    // 2x on the 64..256-bin passes of the two-pass sort.
+    const int staged = rounds == 1 && NB >= 32 && NB <= g_stage_max_bins ? 1 : 0;
     const size_t lds = (size_t)(NB + 40 + waves * NB + (staged ? NB + 2 * kSubTile : 0)) * sizeof(int);
     if (lds > 64 * 1024) {
         static bool attr_set[2] = {false, false};
