@@ -797,9 +797,10 @@ int choose_assign_variant(int64_t total_points) {
 void set_assign_variant_override(int v) { g_variant_override = v; }
 
 // Streaming kernel or sweeping kernel for few centroids?  Measured on MI355X: with X well
-// beyond the last-level cache (256 MiB) the streaming kernel's continuous copies win by
-// ~20% up to two centroid tiles; below that size, and from three tiles on, the sweeping
-// kernel's bulk prologue loads are as fast or faster.  g_stream_option: -1 = that rule,
+// beyond the last-level cache (256 MiB) and rows of at least 64 bytes the streaming kernel's
+// continuous copies win by 10-20% while C fits one LDS stage (d = 64: up to 128 centroids,
+// d = 128: up to 64); for cache-sized X, narrow rows, or more centroids the sweeping kernel's
+// bulk prologue loads and two points per lane are as fast or faster.  g_stream_option: -1 = that rule,
 // 0 = never, 1 = whenever the centroids fit one LDS stage (FK_ASSIGN_STREAM sets the start
 // value; fk_set_option("assign_stream", v) changes it).
 static int g_stream_option = [] {
@@ -815,7 +816,11 @@ bool assign_uses_stream_kernel(const Geometry& g) {
     if (g.ktiles > st || g_stream_option == 0) return false;
     if (g_stream_option > 0) return true;
     const int64_t x_bytes = (int64_t)g.B * g.N * g.d * 2;
-    return g.ktiles <= 2 && x_bytes >= ((int64_t)384 << 20);
+    if (x_bytes < ((int64_t)384 << 20) || g.d <= 32) return false;
+    // rows of 128 or 256 bytes are stored swizzled (conflict-free operand reads): every shape
+    // that fits a stage; other widths: two tiles below 128-byte rows, one above
+    const int limit = (g.d == 64 || g.d == 128) ? st : (g.d < 64 ? 2 : 1);
+    return g.ktiles <= limit;
 }
 
 template <bool BF, int DCH>

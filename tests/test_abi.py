@@ -82,7 +82,9 @@ def test_plan_describes_the_choice_per_shape():
     assert "mfma_sweep(variant=0" in fk.fk_plan(1, 300000, 128, 1024, f16)      # least idle last round
     assert "mfma_stream" in fk.fk_plan(1, 1 << 24, 64, 16, f16)             # X far beyond the cache
     assert "mfma_sweep" in fk.fk_plan(1, 1 << 20, 64, 16, f16)              # X cache-sized: bulk loads
-    assert "mfma_sweep" in fk.fk_plan(1, 1 << 24, 64, 100, f16)             # four centroid tiles
+    assert "mfma_stream" in fk.fk_plan(1, 1 << 24, 64, 100, f16)            # still one LDS stage at d = 64
+    assert "mfma_sweep" in fk.fk_plan(1, 1 << 24, 128, 100, f16)            # more than a stage at d = 128
+    assert "mfma_sweep" in fk.fk_plan(1, 1 << 25, 32, 16, f16)              # narrow rows
     assert "mfma_wide(chunks=32" in fk.fk_plan(1, 1 << 20, 512, 65536, f16)
     assert "sort=2pass" in fk.fk_plan(1, 1 << 20, 512, 65536, f16)
     # few clusters: the sort-free update fused into the assignment pass, unless switched off
