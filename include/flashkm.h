@@ -178,6 +178,8 @@ fk_status fk_standard_update(const void* X, const int32_t* assign, const float* 
  *                        persistent streaming assign kernel
  *   "sort_stage_bins" n  the counting sort's scatter orders its tile in LDS before writing
  *                        when a pass has 32..n bins (default 1024; 0 = never)
+ *   "sort_min_rounds" r  sort workgroups own at least r sub-tiles of 4096 keys (the rule gives
+ *                        one up to 2^24 keys); changes fk_workspace_bytes, so set it before sizing
  *   "fused_update"   0   few clusters: do not take the sort-free update below
  * Few clusters (FK_F16 / FK_BF16, K <= 32, d <= 128): fk_lloyd_iter computes assignment and
  * per-workgroup tables of sums in ONE pass over X (a one-hot MFMA adds each 32-point batch into

@@ -55,6 +55,8 @@ static int ceil_log2(int v) {
     return b;
 }
 
+static int g_sort_min_rounds = 0;   // fk_set_option("sort_min_rounds")
+
 bool make_geometry(int B, int64_t N, int d, int K, fk_dtype t, Geometry* g) {
     if (B < 1 || N < 1 || K < 1 || K > 65536 || d < 8 || d > 512 || (d % 8) != 0) return false;
     if (t != FK_F32 && t != FK_F16 && t != FK_BF16) return false;
@@ -84,6 +86,11 @@ bool make_geometry(int B, int64_t N, int d, int K, fk_dtype t, Geometry* g) {
     (void)nbmax;
     const int64_t max_blocks = g->sort_passes == 1 ? 4096 : 65536;
     int64_t T = 4096 * cdiv(N, (int64_t)4096 * max_blocks);
+    // (an instance of at most 4096 keys is one tile: the scatter kernel then counts for itself
+    // and no histogram / scan kernel runs)
+    // testing aid: larger tiles than the rule would pick (the several-rounds-per-workgroup form
+    // of the sort kernels is otherwise only reached beyond 2^24 keys)
+    if (g_sort_min_rounds > 1 && T < (int64_t)4096 * g_sort_min_rounds) T = (int64_t)4096 * g_sort_min_rounds;
     g->sort_tile = (int)T;
     g->sort_blocks = (int)cdiv(N, T);
     // rows reduced into one partial row: 256 by one wave, or, for N above 4M points, N/4096 by
@@ -278,6 +285,10 @@ int fk_set_option(const char* name, int value) {
     }
     if (name && strcmp(name, "assign_stream") == 0 && value >= -1 && value <= 1) {
         set_assign_stream_option(value);
+        return FK_OK;
+    }
+    if (name && strcmp(name, "sort_min_rounds") == 0 && value >= -1 && value <= 64) {
+        g_sort_min_rounds = value;
         return FK_OK;
     }
     if (name && strcmp(name, "sort_stage_bins") == 0 && value >= -1 && value <= 2048) {

@@ -75,9 +75,10 @@ __device__ int block_exclusive_scan(int* v, int n, int* scratch) {
 // ------------------------------------------------------------------------------------
 // Tiling shared by the histogram and scatter kernels: a workgroup of WAVES waves (8, or 4
 // when the per-wave counters of a wide digit would not fit in LDS) owns `rounds` consecutive
-// sub-tiles of 4096 keys; inside a sub-tile wave w owns 4096/WAVES consecutive keys as
-// batches of 64, batch j at offset j*64 + lane.  All loads of a round are issued before any
-// is used.
+// sub-tiles of 4096 keys.  With one round, wave w owns 4096/WAVES consecutive keys as batches
+// of 64, batch j at offset j*64 + lane; with several, the scatter gives each wave `rounds` such
+// runs back to back (the histogram only counts, any partition of the tile serves it).  All
+// loads of a round are issued before any is used.
 constexpr int kSubTile = 4096;
 
 // Keys come back clamped to [0, kmax]; -1 marks a lane past the end of the array.
@@ -190,7 +191,7 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_scatter_kernel(
     const int32_t* __restrict__ H, const int32_t* __restrict__ tot,
     int32_t* __restrict__ vals_out, int32_t* __restrict__ keys_out,
     int32_t* __restrict__ seg_off, int32_t* __restrict__ item_off, int64_t N, int rounds,
-    int NB, int shift, int mask, int kmax, int nbits, int R, int staged) {
+    int NB, int shift, int mask, int kmax, int nbits, int R, int staged, int solo) {
     constexpr int kSortThreads = kSortWaves * 64, kBatches = kSubTile / kSortThreads;
     extern __shared__ int lds[];
     int* off = lds;                    // [NB]
@@ -211,28 +212,45 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_scatter_kernel(
 
     // first round's keys are requested before the offset scans below need them
     int k[kBatches];
-    const int64_t base0 = (int64_t)blk * rounds * kSubTile + wave * (kBatches * 64);
+    // a wave owns `rounds` consecutive batches-of-8 (contiguous in the input, so that wave order
+    // is input order and the sort stays stable with several rounds)
+    const int64_t base0 = (int64_t)blk * rounds * kSubTile + (int64_t)wave * rounds * (kBatches * 64);
+    constexpr int kRoundStep = kBatches * 64;
     load_round(keys, base0, N, lane, kmax, k);
 
-    if (item_off && blk == 0) {
-        // exclusive scan of ceil(n_k / R): where each cluster's items start
-        for (int i = tid; i < NB; i += kSortThreads) off[i] = (tot[i] + R - 1) / R;
+    // Bin totals -> off[] (exclusive scan: where each bin starts in the output), plus the
+    // segment and item tables when asked for.  The totals come from the scan kernel, or, when
+    // one workgroup sorts the whole instance (solo), from its own per-wave counts after the
+    // counting pass -- no histogram or scan kernel runs then.
+    auto offsets_from_totals = [&]() {
+        auto total_of = [&](int i) -> int {
+            if (!solo) return tot[i];
+            int t = 0;
+            for (int w = 0; w < kSortWaves; ++w) t += wcnt[w * NB + i];
+            return t;
+        };
+        if (item_off && blk == 0) {
+            // exclusive scan of ceil(n_k / R): where each cluster's items start
+            for (int i = tid; i < NB; i += kSortThreads) off[i] = (total_of(i) + R - 1) / R;
+            __syncthreads();
+            const int items = block_exclusive_scan(off, NB, scratch);
+            int32_t* io = item_off + (size_t)b * (NB + 1);
+            for (int i = tid; i < NB; i += kSortThreads) io[i] = off[i];
+            if (tid == 0) io[NB] = items;
+            __syncthreads();
+        }
+        for (int i = tid; i < NB; i += kSortThreads) off[i] = total_of(i);
         __syncthreads();
         const int total = block_exclusive_scan(off, NB, scratch);
-        int32_t* io = item_off + (size_t)b * (NB + 1);
-        for (int i = tid; i < NB; i += kSortThreads) io[i] = off[i];
-        if (tid == 0) io[NB] = total;
-        __syncthreads();
-    }
-    for (int i = tid; i < NB; i += kSortThreads) off[i] = tot[i];
+        if (seg_off && blk == 0) {
+            int32_t* so = seg_off + (size_t)b * (NB + 1);
+            for (int i = tid; i < NB; i += kSortThreads) so[i] = off[i];
+            if (tid == 0) so[NB] = total;
+        }
+    };
     for (int i = tid; i < kSortWaves * NB; i += kSortThreads) wcnt[i] = 0;
     __syncthreads();
-    const int total = block_exclusive_scan(off, NB, scratch);
-    if (seg_off && blk == 0) {
-        int32_t* so = seg_off + (size_t)b * (NB + 1);
-        for (int i = tid; i < NB; i += kSortThreads) so[i] = off[i];
-        if (tid == 0) so[NB] = total;
-    }
+    if (!solo) offsets_from_totals();
 
     int* mine = wcnt + wave * NB;
     const uint64_t lt = lanemask_lt();
@@ -259,6 +277,7 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_scatter_kernel(
             __builtin_amdgcn_wave_barrier();
         }
         __syncthreads();
+        if (solo) offsets_from_totals();
         int v[kBatches];
         if (vals_in) {
 #pragma unroll
@@ -294,7 +313,8 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_scatter_kernel(
             __syncthreads();
             // global position = position in the tile + (global start of the tile's run of the bin
             // - its start inside the tile)
-            for (int i = tid; i < NB; i += kSortThreads) gdel[i] = off[i] + H[(size_t)i * nb] - gdel[i];
+            for (int i = tid; i < NB; i += kSortThreads)
+                gdel[i] = off[i] + (solo ? 0 : H[(size_t)i * nb]) - gdel[i];
             __syncthreads();
             const int64_t tile0 = (int64_t)blk * kSubTile;
             const int live = (int)min((int64_t)kSubTile, N - tile0);
@@ -308,7 +328,7 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_scatter_kernel(
         }
         // counts -> start positions: global bin offset + earlier workgroups + earlier waves
         for (int i = tid; i < NB; i += kSortThreads) {
-            int run = off[i] + H[(size_t)i * nb];
+            int run = off[i] + (solo ? 0 : H[(size_t)i * nb]);
             for (int w = 0; w < kSortWaves; ++w) {
                 const int t = wcnt[w * NB + i];
                 wcnt[w * NB + i] = run;
@@ -348,15 +368,16 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_scatter_kernel(
     // pass 1: per-wave digit counts
     rank_round(true);
     for (int r = 1; r < rounds; ++r) {
-        const int64_t base = base0 + (int64_t)r * kSubTile;
+        const int64_t base = base0 + (int64_t)r * kRoundStep;
         if (base >= N) break;
         load_round(keys, base, N, lane, kmax, k);
         rank_round(true);
     }
     __syncthreads();
+    if (solo) offsets_from_totals();
     // counts -> start positions: global bin offset + earlier workgroups + earlier waves
     for (int i = tid; i < NB; i += kSortThreads) {
-        int run = off[i] + H[(size_t)i * nb];
+        int run = off[i] + (solo ? 0 : H[(size_t)i * nb]);
         for (int w = 0; w < kSortWaves; ++w) {
             const int t = wcnt[w * NB + i];
             wcnt[w * NB + i] = run;
@@ -366,7 +387,7 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_scatter_kernel(
     __syncthreads();
     // pass 2: write, advancing the wave's cursors batch by batch
     for (int r = 0; r < rounds; ++r) {
-        const int64_t base = base0 + (int64_t)r * kSubTile;
+        const int64_t base = base0 + (int64_t)r * kRoundStep;
         if (base >= N) break;
         load_round(keys, base, N, lane, kmax, k);
         rank_round(false);
@@ -458,21 +479,25 @@ static fk_status sort_pass(const Geometry& g, const Workspace& w, const int32_t*
     int32_t* tot = w.digit_off;
     dim3 grid(g.sort_blocks, g.B);
     const bool wide = NB > 1024;       // 8 waves of counters would not fit in LDS
-    const size_t hist_lds = (size_t)NB * (NB <= 64 ? 16 : 1) * sizeof(int);
-    if (wide)
-        hipLaunchKernelGGL(sort_hist_kernel<4>, grid, dim3(256), hist_lds, s, keys, H, g.N,
-                           rounds, NB, shift, mask, g.K - 1, nbits);
-    else
-        hipLaunchKernelGGL(sort_hist_kernel<8>, grid, dim3(512), hist_lds, s, keys, H, g.N,
-                           rounds, NB, shift, mask, g.K - 1, nbits);
-    FK_HIP(hipGetLastError());
-    if (g.sort_blocks > 512)
-        hipLaunchKernelGGL(sort_binscan_kernel<256>, dim3((unsigned)NB, g.B), dim3(256), 0, s, H,
-                           tot, g.sort_blocks, NB);
-    else
-        hipLaunchKernelGGL(sort_binscan_kernel<64>, dim3((unsigned)cdiv(NB, 4), g.B), dim3(256), 0,
-                           s, H, tot, g.sort_blocks, NB);
-    FK_HIP(hipGetLastError());
+    // one workgroup per instance: the scatter kernel counts for itself
+    const int solo = g.sort_blocks == 1 ? 1 : 0;
+    if (!solo) {
+        const size_t hist_lds = (size_t)NB * (NB <= 64 ? 16 : 1) * sizeof(int);
+        if (wide)
+            hipLaunchKernelGGL(sort_hist_kernel<4>, grid, dim3(256), hist_lds, s, keys, H, g.N,
+                               rounds, NB, shift, mask, g.K - 1, nbits);
+        else
+            hipLaunchKernelGGL(sort_hist_kernel<8>, grid, dim3(512), hist_lds, s, keys, H, g.N,
+                               rounds, NB, shift, mask, g.K - 1, nbits);
+        FK_HIP(hipGetLastError());
+        if (g.sort_blocks > 512)
+            hipLaunchKernelGGL(sort_binscan_kernel<256>, dim3((unsigned)NB, g.B), dim3(256), 0, s, H,
+                               tot, g.sort_blocks, NB);
+        else
+            hipLaunchKernelGGL(sort_binscan_kernel<64>, dim3((unsigned)cdiv(NB, 4), g.B), dim3(256), 0,
+                               s, H, tot, g.sort_blocks, NB);
+        FK_HIP(hipGetLastError());
+    }
     const int waves = wide ? 4 : 8;
     // One tile per workgroup: sorted in LDS first, then written in contiguous runs.  Measured
     // (2^20 .. 2^25 keys): pays from 32 bins (below that a wave's stores already fall into few
@@ -491,11 +516,11 @@ static fk_status sort_pass(const Geometry& g, const Workspace& w, const int32_t*
     if (wide)
         hipLaunchKernelGGL(sort_scatter_kernel<4>, grid, dim3(256), lds, s, keys, vals_in, H, tot,
                            vals_out, keys_out, seg_off, item_off, g.N, rounds, NB, shift, mask,
-                           g.K - 1, nbits, g.rows_per_item, staged);
+                           g.K - 1, nbits, g.rows_per_item, staged, solo);
     else
         hipLaunchKernelGGL(sort_scatter_kernel<8>, grid, dim3(512), lds, s, keys, vals_in, H, tot,
                            vals_out, keys_out, seg_off, item_off, g.N, rounds, NB, shift, mask,
-                           g.K - 1, nbits, g.rows_per_item, staged);
+                           g.K - 1, nbits, g.rows_per_item, staged, solo);
     FK_HIP(hipGetLastError());
     return FK_OK;
 }

@@ -136,6 +136,26 @@ def test_sort_inverse_is_the_stable_argsort(B, N, K):
         assert (so[b] == ref_off).all()
 
 
+@pytest.mark.parametrize("B,N,K", [(1, 50000, 1), (2, 30000, 16), (1, 100000, 1000), (1, 70001, 2049),
+                                   (1, 200000, 65536), (1, 40000, 2048), (1, 9000, 300)])
+@pytest.mark.parametrize("rounds", [2, 3])
+def test_sort_inverse_with_several_sub_tiles_per_workgroup(B, N, K, rounds):
+    """The form of the sort kernels in which a workgroup owns several 4096-key sub-tiles (taken
+    by itself only beyond 2^24 keys, or for a whole small instance) must stay stable."""
+    g = torch.Generator().manual_seed(N + K + rounds)
+    a = torch.randint(0, K, (B, N), generator=g).to(torch.int32)
+    try:
+        fk.fk_set_option("sort_min_rounds", rounds)
+        si, so = fk.fk_sort_inverse(a.to(DEV), K)
+    finally:
+        fk.fk_set_option("sort_min_rounds", -1)
+    si, so = si.cpu().numpy(), so.cpu().numpy()
+    for b in range(B):
+        ab = a[b].numpy()
+        assert (si[b] == np.argsort(ab, kind="stable")).all()
+        assert (so[b] == np.concatenate([[0], np.cumsum(np.bincount(ab, minlength=K))])).all()
+
+
 def test_sort_inverse_single_cluster_and_sorted_input():
     a = torch.zeros((1, 70000), dtype=torch.int32)
     si, so = fk.fk_sort_inverse(a.to(DEV), 8)
