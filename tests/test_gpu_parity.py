@@ -93,6 +93,29 @@ def test_streaming_and_sweeping_assign_kernels_agree(dtype, B, N, d, K):
         parity.check_assign(parity.widen(X[b]), parity.widen(C0.to(dtype)[b]), a1[b].cpu().numpy())
 
 
+@pytest.mark.parametrize("dtype,B,N,d,K", [(torch.float16, 1, 5000, 128, 1000), (torch.bfloat16, 2, 3000, 64, 300),
+                                          (torch.float16, 1, 2100, 32, 2500), (torch.float16, 1, 700, 96, 130)])
+def test_every_tile_shape_of_the_sweeping_kernel_gives_the_same_answer(dtype, B, N, d, K):
+    """The four compiled tile shapes differ in how points are split over waves and workgroups,
+    not in the arithmetic: identical assignments and distances, and parity with the oracle."""
+    w, X, _, C0 = _problem(dtype, B, N, d, K, seed=480 + N + K)
+    C = C0.to(dtype).to(DEV)
+    res = []
+    try:
+        fk.fk_set_option("assign_stream", 0)
+        for v in (0, 1, 2, 3):
+            fk.fk_set_option("assign_variant", v)
+            assert f"variant={v}" in fk.fk_plan(B, N, d, K, dtype)
+            res.append(fk.fk_assign(X.to(DEV), C, min_dist=True))
+    finally:
+        fk.fk_set_option("assign_variant", -1)
+        fk.fk_set_option("assign_stream", -1)
+    for a, md in res[1:]:
+        assert torch.equal(a, res[0][0]) and torch.equal(md, res[0][1])
+    for b in range(B):
+        parity.check_assign(parity.widen(X[b]), parity.widen(C0.to(dtype)[b]), res[0][0][b].cpu().numpy())
+
+
 def test_assign_exact_duplicates_go_to_lowest_index():
     w, X, _, C0 = _problem(torch.float16, 1, 2000, 128, 96, seed=7)
     C = C0.to(torch.float16)
