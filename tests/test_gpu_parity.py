@@ -40,6 +40,10 @@ ASSIGN_CASES = [
     (torch.float32, 2, 777, 8, 3),
     (torch.float32, 1, 500, 128, 130),
     (torch.float32, 1, 400, 40, 7),
+    # fp32 beyond 2^18 points: one point per thread, whole centroid tiles per workgroup
+    (torch.float32, 1, 270000, 64, 40),
+    (torch.float32, 2, 140000, 24, 9),
+    (torch.float32, 1, 262200, 128, 12),
     # wide features (128 < d <= 512)
     (torch.float16, 1, 3000, 256, 300),
     (torch.bfloat16, 2, 1500, 512, 200),
@@ -476,6 +480,7 @@ FEW_CLUSTER_CASES = [
     (torch.float16, 1, 31, 64, 4, 0.0),           # less than one batch
     (torch.float16, 1, 1, 16, 1, 0.0),            # one point, one cluster
     (torch.bfloat16, 1, 33, 32, 32, 0.0),         # K about N: most clusters nearly empty
+    (torch.float16, 1100, 40, 8, 3, 0.0),         # more instances than workgroups to share: one each
 ]
 
 
