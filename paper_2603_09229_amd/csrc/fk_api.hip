@@ -81,10 +81,10 @@ bool make_geometry(int B, int64_t N, int d, int K, fk_dtype t, Geometry* g) {
     }
     // sort workgroups own whole sub-tiles of 4096 keys, one each (keys then stay in registers
     // between the scatter's two passes) until the table of per-workgroup histograms gets too
-    // large: at most 4096 workgroups per instance for the single pass (up to 2048 bins),
-    // 65536 for the two-pass sort (up to 256 bins per pass)
+    // large: at most 4096 workgroups per instance with more than 256 bins, 65536 with fewer
+    // (every pass of the two-pass sort, and the single pass for K <= 256)
     (void)nbmax;
-    const int64_t max_blocks = g->sort_passes == 1 ? 4096 : 65536;
+    const int64_t max_blocks = (g->sort_passes == 1 && K > 256) ? 4096 : 65536;
     int64_t T = 4096 * cdiv(N, (int64_t)4096 * max_blocks);
     // (an instance of at most 4096 keys is one tile: the scatter kernel then counts for itself
     // and no histogram / scan kernel runs)
