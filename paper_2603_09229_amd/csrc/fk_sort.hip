@@ -217,6 +217,15 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_scatter_kernel(
     const int64_t base0 = (int64_t)blk * rounds * kSubTile + (int64_t)wave * rounds * (kBatches * 64);
     constexpr int kRoundStep = kBatches * 64;
     load_round(keys, base0, N, lane, kmax, k);
+    // this workgroup's column of the scanned histogram table (one entry per bin, a cache line
+    // apart): requested now, needed only after the counting pass
+    constexpr int kHPer = 2048 / kSortThreads;
+    int hcol[kHPer];
+#pragma unroll
+    for (int q = 0; q < kHPer; ++q) {
+        const int i = tid + q * kSortThreads;
+        hcol[q] = (!solo && i < NB) ? H[(size_t)i * nb] : 0;
+    }
 
     // Bin totals -> off[] (exclusive scan: where each bin starts in the output), plus the
     // segment and item tables when asked for.  The totals come from the scan kernel, or, when
@@ -313,8 +322,11 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_scatter_kernel(
             __syncthreads();
             // global position = position in the tile + (global start of the tile's run of the bin
             // - its start inside the tile)
-            for (int i = tid; i < NB; i += kSortThreads)
-                gdel[i] = off[i] + (solo ? 0 : H[(size_t)i * nb]) - gdel[i];
+#pragma unroll
+            for (int q = 0; q < kHPer; ++q) {
+                const int i = tid + q * kSortThreads;
+                if (i < NB) gdel[i] = off[i] + hcol[q] - gdel[i];
+            }
             __syncthreads();
             const int64_t tile0 = (int64_t)blk * kSubTile;
             const int live = (int)min((int64_t)kSubTile, N - tile0);
@@ -327,12 +339,16 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_scatter_kernel(
             return;
         }
         // counts -> start positions: global bin offset + earlier workgroups + earlier waves
-        for (int i = tid; i < NB; i += kSortThreads) {
-            int run = off[i] + (solo ? 0 : H[(size_t)i * nb]);
-            for (int w = 0; w < kSortWaves; ++w) {
-                const int t = wcnt[w * NB + i];
-                wcnt[w * NB + i] = run;
-                run += t;
+#pragma unroll
+        for (int q = 0; q < kHPer; ++q) {
+            const int i = tid + q * kSortThreads;
+            if (i < NB) {
+                int run = off[i] + hcol[q];
+                for (int w = 0; w < kSortWaves; ++w) {
+                    const int t = wcnt[w * NB + i];
+                    wcnt[w * NB + i] = run;
+                    run += t;
+                }
             }
         }
         __syncthreads();
@@ -376,12 +392,16 @@ __global__ __launch_bounds__(kSortWaves * 64) void sort_scatter_kernel(
     __syncthreads();
     if (solo) offsets_from_totals();
     // counts -> start positions: global bin offset + earlier workgroups + earlier waves
-    for (int i = tid; i < NB; i += kSortThreads) {
-        int run = off[i] + (solo ? 0 : H[(size_t)i * nb]);
-        for (int w = 0; w < kSortWaves; ++w) {
-            const int t = wcnt[w * NB + i];
-            wcnt[w * NB + i] = run;
-            run += t;
+#pragma unroll
+    for (int q = 0; q < kHPer; ++q) {
+        const int i = tid + q * kSortThreads;
+        if (i < NB) {
+            int run = off[i] + hcol[q];
+            for (int w = 0; w < kSortWaves; ++w) {
+                const int t = wcnt[w * NB + i];
+                wcnt[w * NB + i] = run;
+                run += t;
+            }
         }
     }
     __syncthreads();
