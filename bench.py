@@ -58,6 +58,9 @@ def main() -> int:
                     help="time both sides of the host's other kernel choices over a grid of shapes: "
                          "streaming vs sweeping assign kernel for few centroids, LDS-staged vs "
                          "direct scatter in the counting sort (prints one JSON line)")
+    ap.add_argument("--clock-trace", action="store_true",
+                    help="loop the assign kernel (and a device copy) for a few seconds each while "
+                         "sampling the shader clock with rocm-smi (prints one JSON line)")
     ap.add_argument("--general-update", action="store_true",
                     help="few-cluster shapes: use the general assign + sort-inverse path instead "
                          "of the fused one-hot pass (for comparing the two)")
@@ -89,6 +92,8 @@ def main() -> int:
         return compare_standard(torch, fk, wl, dev)
     if args.sweep_choices:
         return sweep_choices(torch, fk, dev)
+    if args.clock_trace:
+        return clock_trace(torch, fk, dev)
     if args.general_update:
         fk.fk_set_option("fused_update", 0)
     w = short[args.workload]
@@ -287,6 +292,58 @@ def compare_standard(torch, fk, wl, dev):
                         "speedup_onehot_over_sort_inverse": t_si / t_oh})
         out["update"].append(row)
         del X, lab
+    print(json.dumps(out))
+    return 0
+
+
+def clock_trace(torch, fk, dev):
+    """What shader clock the part holds under each kind of load (rocm-smi, sampled twice a second
+    from a side thread while the kernel is launched back to back)."""
+    import re
+    import subprocess
+    import threading
+
+    def sclk():
+        try:
+            out = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=10).stdout
+            m = re.search(r"sclk clock level: \d+: \((\d+)Mhz\)", out)
+            return int(m.group(1)) if m else None
+        except Exception:
+            return None
+
+    def loop(fn, secs=3.0):
+        seen, stop = [], threading.Event()
+
+        def sampler():
+            while not stop.is_set():
+                v = sclk()
+                if v is not None:
+                    seen.append(v)
+                time.sleep(0.5)
+        th = threading.Thread(target=sampler)
+        th.start()
+        t0 = time.time()
+        while time.time() - t0 < secs:
+            for _ in range(20):
+                fn()
+            torch.cuda.synchronize()
+        stop.set()
+        th.join()
+        return seen[1:] if len(seen) > 1 else seen          # the first sample may predate the load
+
+    N, d = 1 << 20, 128
+    X = (torch.randn(1, N, d, device=dev) * 4).half()
+    out = {"metric": "shader_clock_under_load_mhz", "idle": sclk(), "loads": []}
+    for K in (16384, 1024, 256):
+        C = (torch.randn(1, K, d, device=dev) * 4).half()
+        ws = fk.make_workspace(1, N, d, K, torch.float16, dev)
+        a = torch.empty((1, N), dtype=torch.int32, device=dev)
+        us = _time_us(torch, lambda: fk.fk_assign(X, C, ws=ws, out=a))
+        out["loads"].append({"load": f"fk_assign N=2^20 d=128 K={K} fp16", "sclk_mhz": loop(lambda: fk.fk_assign(X, C, ws=ws, out=a)),
+                             "tflops": 2.0 * N * K * d / us / 1e6})
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    out["loads"].append({"load": "1 GiB device-to-device copy", "sclk_mhz": loop(lambda: dst.copy_(src))})
     print(json.dumps(out))
     return 0
 
