@@ -27,9 +27,13 @@
  *     enqueue work on it and return without waiting, except fk_lloyd_ooc.  The in-core calls
  *     enqueue kernels only (no memset, no allocation), so after one eager call for a shape
  *     they can be recorded into a HIP graph by stream capture and replayed.
- *   - Supported shapes: 1 <= K <= 65536, 1 <= N, B*N < 2^31, 1 <= B <= 65535,
- *     d a multiple of 8 with 8 <= d <= 512.  Anything else returns FK_EUNSUPPORTED or
- *     FK_EINVAL; there is no fallback path.
+ *   - Supported shapes: 1 <= K <= 65536, 1 <= N, B*N < 2^31, 1 <= B <= 65535, 1 <= d <= 512.
+ *     The kernels work on rows whose width is a multiple of 8; for any other d the in-core
+ *     entry points first copy X and C into zero-padded rows inside the workspace (zeros change
+ *     no distance and no mean; costs one extra pass over X per call and room for the copy,
+ *     which fk_workspace_bytes includes) and copy the centroids back without the padding.
+ *     fk_lloyd_ooc and the fk_standard_* comparators need d to be a multiple of 8.  Anything
+ *     else returns FK_EUNSUPPORTED or FK_EINVAL; there is no fallback path.
  *   - Every function returns an fk_status; on failure fk_last_error() holds a message for
  *     the calling thread.  Nothing throws or aborts.
  */

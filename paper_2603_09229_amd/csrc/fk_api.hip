@@ -57,8 +57,10 @@ static int ceil_log2(int v) {
 
 static int g_sort_min_rounds = 0;   // fk_set_option("sort_min_rounds")
 
-bool make_geometry(int B, int64_t N, int d, int K, fk_dtype t, Geometry* g) {
-    if (B < 1 || N < 1 || K < 1 || K > 65536 || d < 8 || d > 512 || (d % 8) != 0) return false;
+bool make_geometry(int B, int64_t N, int d_user, int K, fk_dtype t, Geometry* g) {
+    if (B < 1 || N < 1 || K < 1 || K > 65536 || d_user < 1 || d_user > 512) return false;
+    const int d = (d_user + 7) / 8 * 8;
+    g->d_user = d_user;
     if (t != FK_F32 && t != FK_F16 && t != FK_BF16) return false;
     if ((int64_t)B * N >= ((int64_t)1 << 31)) return false;
     if (B > 65535) return false;                 // instances are the y dimension of every launch
@@ -143,6 +145,11 @@ Workspace carve(const Geometry& g, void* base) {
     w.partial = (float*)take((size_t)g.B * std::max((size_t)g.max_items, fused_rows) * g.d * 4);
     if (g.fused_grid_cap > 0) w.wg_counts = (int32_t*)take((size_t)g.B * fused_rows * 4);
     w.sums = (float*)take(BKd * 4);
+    if (g.d != g.d_user) {
+        w.x_pad = take(BN * g.d * elem_size(g.t));
+        w.c_pad_f32 = (float*)take(BKd * 4);
+        w.c_pad_lp = take(BKd * elem_size(g.t));
+    }
     w.bytes = off;
     return w;
 }
@@ -182,7 +189,7 @@ static fk_status check_common(const char* fn, int B, int64_t N, int d, int K, fk
         return FK_EINVAL;
     }
     if (!make_geometry(B, N, d, K, t, g)) {
-        set_error("%s: unsupported shape B=%d N=%lld d=%d K=%d (need d%%8==0, 8<=d<=512, K<=65536, B<=65535, B*N<2^31)",
+        set_error("%s: unsupported shape B=%d N=%lld d=%d K=%d (need 1<=d<=512, K<=65536, B<=65535, B*N<2^31)",
                   fn, B, (long long)N, d, K);
         return FK_EUNSUPPORTED;
     }
@@ -338,6 +345,10 @@ int fk_plan(int B, int64_t N, int d, int K, fk_dtype t, char* buf, size_t buf_by
              assign, g.ktiles, g.sort_passes, g.sort_tile, g.sort_blocks,
              g.waves_per_item == 4 ? "workgroup_per_item" : "wave_per_item", g.rows_per_item,
              (long long)g.max_items, carve(g, nullptr).bytes);
+    if (g.d != g.d_user) {
+        const size_t n = strlen(buf);
+        if (n + 1 < buf_bytes) snprintf(buf + n, buf_bytes - n, " rows_padded=%d->%d", g.d_user, g.d);
+    }
     return FK_OK;
 }
 
@@ -358,6 +369,13 @@ fk_status fk_assign(const void* X, const void* C, int32_t* assign, float* min_di
     FK_OPTIONAL_PTR("fk_assign", min_dist);
     hipStream_t s = (hipStream_t)stream;
     const Workspace w = carve(g, ws);
+    if (g.d != g.d_user) {
+        // rows that are not a multiple of 8 wide: work on zero-padded copies
+        FK_TRY(launch_copy_rows(X, w.x_pad, (int64_t)B * N, g.d_user, g.d, (int)elem_size(t), s));
+        FK_TRY(launch_copy_rows(C, w.c_pad_lp, (int64_t)B * K, g.d_user, g.d, (int)elem_size(t), s));
+        X = w.x_pad;
+        C = w.c_pad_lp;
+    }
     if (t == FK_F32) return launch_assign(g, X, C, nullptr, assign, min_dist, s);
     FK_TRY(launch_prepare_centroids(g, C, w.c_frag, w.c_bias, s));
     return launch_assign(g, X, w.c_frag, w.c_bias, assign, min_dist, s);
@@ -402,18 +420,31 @@ fk_status fk_update(const void* X, const int32_t* assign, const float* C_prev_f3
     FK_OPTIONAL_PTR("fk_update", C_out_lp);
     FK_REQUIRE_PTR("fk_update", counts);
     const Workspace w = carve(g, ws);
+    hipStream_t s = (hipStream_t)stream;
+    const bool pad = g.d != g.d_user;
+    if (pad) {
+        FK_TRY(launch_copy_rows(X, w.x_pad, (int64_t)B * N, g.d_user, g.d, (int)elem_size(t), s));
+        FK_TRY(launch_copy_rows(C_prev_f32, w.c_pad_f32, (int64_t)B * K, g.d_user, g.d, 4, s));
+        X = w.x_pad;
+    }
     FinalizeArgs fa;
-    fa.C_prev_f32 = C_prev_f32;
-    fa.C_out_f32 = C_out_f32;
-    fa.C_out_lp = C_out_lp;
+    fa.C_prev_f32 = pad ? w.c_pad_f32 : C_prev_f32;
+    fa.C_out_f32 = pad ? w.c_pad_f32 : C_out_f32;
+    fa.C_out_lp = pad ? (C_out_lp ? w.c_pad_lp : nullptr) : C_out_lp;
     fa.c_frag = nullptr;
     fa.c_bias = nullptr;
     fa.counts = counts;
     fa.sums = nullptr;
     fa.accumulate = false;
     fa.normalise = true;
-    timer_mark((hipStream_t)stream, -1);
-    return run_update(g, w, X, assign, fa, (hipStream_t)stream);
+    timer_mark(s, -1);
+    FK_TRY(run_update(g, w, X, assign, fa, s));
+    if (pad) {
+        FK_TRY(launch_copy_rows(w.c_pad_f32, C_out_f32, (int64_t)B * K, g.d, g.d_user, 4, s));
+        if (C_out_lp)
+            FK_TRY(launch_copy_rows(w.c_pad_lp, C_out_lp, (int64_t)B * K, g.d, g.d_user, (int)elem_size(t), s));
+    }
+    return FK_OK;
 }
 
 fk_status fk_standard_assign(const void* X, const void* C, float* D, int32_t* assign, int B,
@@ -421,6 +452,10 @@ fk_status fk_standard_assign(const void* X, const void* C, float* D, int32_t* as
                              void* stream) {
     Geometry g;
     FK_TRY(check_common("fk_standard_assign", B, N, d, K, t, ws, ws_bytes, &g));
+    if (g.d != g.d_user) {
+        set_error("fk_standard_assign: the comparator needs d to be a multiple of 8");
+        return FK_EUNSUPPORTED;
+    }
     FK_REQUIRE_PTR("fk_standard_assign", X);
     FK_REQUIRE_PTR("fk_standard_assign", C);
     FK_REQUIRE_PTR("fk_standard_assign", D);
@@ -435,6 +470,10 @@ fk_status fk_standard_update(const void* X, const int32_t* assign, const float* 
     Geometry g;
     if (!make_geometry(B, N, d, K, t, &g)) {
         set_error("fk_standard_update: unsupported shape B=%d N=%lld d=%d K=%d", B, (long long)N, d, K);
+        return FK_EUNSUPPORTED;
+    }
+    if (g.d != g.d_user) {
+        set_error("fk_standard_update: the comparator needs d to be a multiple of 8");
         return FK_EUNSUPPORTED;
     }
     FK_REQUIRE_PTR("fk_standard_update", X);
@@ -464,6 +503,18 @@ fk_status fk_lloyd_iter(const void* X, float* C_f32, void* C_lp, int32_t* assign
     if (iters == 0) return FK_OK;
     hipStream_t s = (hipStream_t)stream;
     const Workspace w = carve(g, ws);
+    const bool pad = g.d != g.d_user;
+    float* const C_user = C_f32;
+    void* const C_lp_user = C_lp;
+    if (pad) {
+        // rows that are not a multiple of 8 wide: iterate on zero-padded copies of X and C,
+        // copy the centroids back without the padding at the end
+        FK_TRY(launch_copy_rows(X, w.x_pad, (int64_t)B * N, g.d_user, g.d, (int)elem_size(t), s));
+        FK_TRY(launch_copy_rows(C_f32, w.c_pad_f32, (int64_t)B * K, g.d_user, g.d, 4, s));
+        X = w.x_pad;
+        C_f32 = w.c_pad_f32;
+        C_lp = C_lp ? w.c_pad_lp : nullptr;
+    }
     void* lp = C_lp ? C_lp : w.c_lp;
     // what the first assignment consumes: the master rounded to the storage type
     FK_TRY(launch_round_centroids(g, C_f32, t == FK_F32 ? nullptr : lp, w.c_frag, w.c_bias, s));
@@ -493,6 +544,11 @@ fk_status fk_lloyd_iter(const void* X, float* C_f32, void* C_lp, int32_t* assign
         } else {
             FK_TRY(run_update(g, w, X, assign, fa, s));
         }
+    }
+    if (pad) {
+        FK_TRY(launch_copy_rows(C_f32, C_user, (int64_t)B * K, g.d, g.d_user, 4, s));
+        if (C_lp_user)
+            FK_TRY(launch_copy_rows(C_lp, C_lp_user, (int64_t)B * K, g.d, g.d_user, (int)elem_size(t), s));
     }
     return FK_OK;
 }

@@ -88,6 +88,33 @@ fk_status launch_prepare_centroids(const Geometry& g, const void* C_lp, void* c_
     return FK_OK;
 }
 
+// dst[r][j] = j < d_src ? src[r][j] : 0 for j < d_dst: pads rows with zeros (d_dst > d_src) or
+// drops the padding again (d_dst < d_src)
+template <typename T>
+__global__ void copy_rows_kernel(const T* __restrict__ src, T* __restrict__ dst, size_t total,
+                                 int d_src, int d_dst) {
+    for (size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x; o < total;
+         o += (size_t)gridDim.x * blockDim.x) {
+        const size_t r = o / (size_t)d_dst;
+        const int j = (int)(o - r * (size_t)d_dst);
+        dst[o] = j < d_src ? src[r * (size_t)d_src + j] : T(0);
+    }
+}
+
+fk_status launch_copy_rows(const void* src, void* dst, int64_t rows, int d_src, int d_dst,
+                           int elem, hipStream_t s) {
+    const size_t total = (size_t)rows * d_dst;
+    const unsigned blocks = (unsigned)std::min<size_t>(cdiv((int64_t)total, 256), (size_t)1 << 20);
+    if (elem == 2)
+        hipLaunchKernelGGL(copy_rows_kernel<uint16_t>, dim3(blocks), dim3(256), 0, s,
+                           (const uint16_t*)src, (uint16_t*)dst, total, d_src, d_dst);
+    else
+        hipLaunchKernelGGL(copy_rows_kernel<uint32_t>, dim3(blocks), dim3(256), 0, s,
+                           (const uint32_t*)src, (uint32_t*)dst, total, d_src, d_dst);
+    FK_HIP(hipGetLastError());
+    return FK_OK;
+}
+
 __global__ void copy_f32_kernel(const float* __restrict__ src, float* __restrict__ dst, size_t n) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) dst[i] = src[i];

@@ -43,7 +43,10 @@ int device_cu_count();
 struct Geometry {
     int B;
     int64_t N;        // points per instance
-    int d, K;
+    int d, K;         // d: row width the kernels see (a multiple of 8)
+    int d_user;       // row width of the caller's arrays; when it differs from d, X and C are
+                      // first copied into zero-padded rows of width d (zeros change no distance
+                      // and no mean) and the centroids copied back without the padding
     fk_dtype t;
     int dchunks;      // ceil(d / 16)
     int ktiles;       // ceil(K / 32)
@@ -78,6 +81,9 @@ struct Workspace {
     float* partial;      // [B,max(max_items, K*fused_grid_cap),d] per-item segment sums
     int32_t* wg_counts;  // [B,K,fused_grid_cap] per-workgroup counts (few-cluster update only)
     float* sums;         // [B,K,d] accumulated sums (chunked mode)
+    void* x_pad;         // [B,N,d] zero-padded copy of X            (only when d != d_user)
+    float* c_pad_f32;    // [B,K,d] zero-padded fp32 centroids       (only when d != d_user)
+    void* c_pad_lp;      // [B,K,d] zero-padded centroids, dtype t   (only when d != d_user)
     size_t bytes;        // total bytes carved
 };
 
@@ -141,6 +147,12 @@ fk_status launch_stream_update(const Geometry& g, const Workspace& w, const void
                                hipStream_t s);
 bool fused_update_enabled(const Geometry& g);
 void set_fused_update_option(int v);       // 0 = never, otherwise whenever the shape allows
+
+// Row re-layout for widths that are not a multiple of 8: dst[r][j] = j < d_src ? src[r][j] : 0
+// for j < d_dst (padding, d_dst > d_src) or dst[r][j] = src[r][j] for j < d_dst (un-padding,
+// d_dst < d_src).  elem = bytes per element (2 or 4).
+fk_status launch_copy_rows(const void* src, void* dst, int64_t rows, int d_src, int d_dst,
+                           int elem, hipStream_t s);
 
 // Comparator: the standard implementation (paper Algorithm 1); see fk_standard.hip.
 fk_status launch_standard_assign(const Geometry& g, const Workspace& w, const void* X,

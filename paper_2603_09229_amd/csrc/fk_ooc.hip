@@ -21,6 +21,7 @@ struct OocLayout {
 
 static bool ooc_layout(int64_t chunk_rows, int d, int K, fk_dtype t, OocLayout* L, Geometry* g) {
     if (!make_geometry(1, chunk_rows, d, K, t, g)) return false;
+    if (g->d != g->d_user) return false;   // chunks are consumed as they arrive: no padded copy here
     L->chunk_bytes = align_up((size_t)chunk_rows * d * elem_size(t), 256);
     L->core_bytes = align_up(carve(*g, nullptr).bytes, 256);
     L->assign_bytes = align_up((size_t)chunk_rows * 4, 256);

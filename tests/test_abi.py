@@ -35,7 +35,10 @@ def test_workspace_sizes_are_sane():
     assert fk.fk_workspace_bytes(2, 1 << 20, 128, 1024, f16) > base
     assert fk.fk_workspace_bytes(1, 1 << 20, 128, 65536, f16) > base
     assert fk.fk_workspace_bytes(1, 1000, 64, 10, f32) % 256 == 0
-    for bad in [(0, 10, 64, 4), (1, 0, 64, 4), (1, 10, 12, 4), (1, 10, 520, 4), (1, 10, 64, 0),
+    # a width that is not a multiple of 8 is served through a zero-padded copy: room for it
+    assert fk.fk_workspace_bytes(1, 1000, 12, 4, f16) >= fk.fk_workspace_bytes(1, 1000, 16, 4, f16) + 1000 * 16 * 2
+    assert fk.fk_ooc_workspace_bytes(1 << 16, 100, 16, f16) == 0            # not out of core
+    for bad in [(0, 10, 64, 4), (1, 0, 64, 4), (1, 10, 0, 4), (1, 10, 520, 4), (1, 10, 64, 0),
                 (1, 10, 64, 65537), (3, 1 << 30, 64, 4), (65536, 4, 64, 4)]:
         assert fk.fk_workspace_bytes(*bad, f16) == 0
     assert fk.fk_ooc_workspace_bytes(1 << 16, 128, 65536, f16) > 2 * (1 << 16) * 256
@@ -50,7 +53,7 @@ def test_argument_validation_happens_on_the_host():
     rc = L.fk_assign(None, None, None, None, 1, 16, 16, 2, fk.FK_F16, p, 1 << 15, None)
     assert rc == 1 and b"NULL" in L.fk_last_error()
     # unsupported shape
-    rc = L.fk_assign(p, p, p, None, 1, 16, 20, 2, fk.FK_F16, p, 1 << 15, None)
+    rc = L.fk_assign(p, p, p, None, 1, 16, 513, 2, fk.FK_F16, p, 1 << 15, None)
     assert rc == 2
     # workspace too small
     rc = L.fk_update(p, p, p, p, None, p, 1, 1 << 20, 128, 1024, fk.FK_F16, p, 1024, None)
@@ -94,7 +97,8 @@ def test_plan_describes_the_choice_per_shape():
     fk.fk_set_option("fused_update", 0)
     assert "workgroup_per_item" in fk.fk_plan(1, 1 << 24, 64, 16, f16)
     fk.fk_set_option("fused_update", -1)
-    assert fk.fk_plan(1, 100, 12, 3, f16) == "unsupported"
+    assert fk.fk_plan(1, 100, 600, 3, f16) == "unsupported"
+    assert "rows_padded=12->16" in fk.fk_plan(1, 100, 12, 40, f16)
     fk.fk_set_option("assign_variant", 1)
     assert "variant=1" in fk.fk_plan(1, 1 << 20, 128, 1024, f16)
     fk.fk_set_option("assign_variant", -1)

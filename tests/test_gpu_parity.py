@@ -335,10 +335,14 @@ def test_bad_arguments_are_errors_not_crashes():
         fk.fk_assign(X, C, ws=small)
     assert e.value.status == 3
     with pytest.raises(fk.FlashKMError) as e:
-        fk.fk_assign(torch.zeros((1, 8, 12), dtype=torch.float16, device=DEV),
-                     torch.zeros((1, 2, 12), dtype=torch.float16, device=DEV),
+        fk.fk_assign(torch.zeros((1, 8, 520), dtype=torch.float16, device=DEV),
+                     torch.zeros((1, 2, 520), dtype=torch.float16, device=DEV),
                      ws=torch.empty(1 << 20, dtype=torch.uint8, device=DEV))
-    assert e.value.status == 2          # d not a multiple of 8
+    assert e.value.status == 2          # d beyond 512
+    with pytest.raises(fk.FlashKMError) as e:
+        fk.fk_standard_assign(torch.zeros((1, 8, 12), dtype=torch.float16, device=DEV),
+                              torch.zeros((1, 2, 12), dtype=torch.float16, device=DEV))
+    assert e.value.status == 2          # the comparators take no padded widths
     with pytest.raises(ValueError):
         fk.fk_lloyd_ooc(torch.zeros((64, 16), dtype=torch.float16), C[0].float(), 1, dev_ws=small)
 
@@ -462,6 +466,55 @@ def test_iteration_replays_from_a_hip_graph(dtype, N, d, K):
         torch.cuda.synchronize()
         assert torch.equal(C_g, C_e) and torch.equal(a_g, a_e) and torch.equal(n_g, n_e), step
         assert torch.equal(lp_g, lp_e)
+
+
+# ---------------------------------------------------------------------------------------
+# Row widths that are not a multiple of 8: served through zero-padded copies inside the workspace.
+ODD_WIDTH_CASES = [
+    (torch.float16, 1, 3000, 100, 70), (torch.bfloat16, 2, 1500, 3, 5), (torch.float32, 1, 2000, 5, 9),
+    (torch.float16, 1, 4000, 1, 4), (torch.float16, 1, 900, 130, 33), (torch.float32, 1, 700, 509, 12),
+    (torch.bfloat16, 1, 2500, 20, 16), (torch.float16, 1, 1200, 300, 2500), (torch.float32, 1, 1000, 60, 40),
+]
+
+
+@pytest.mark.parametrize("dtype,B,N,d,K", ODD_WIDTH_CASES)
+def test_any_row_width(dtype, B, N, d, K):
+    w, X, lab, C0 = _problem(dtype, B, N, d, K, seed=600 + N + d)
+    Xd = X.to(DEV)
+    keep = Xd.clone()
+    consumed = C0.to(dtype)
+    # assignment alone, with distances
+    a, md = fk.fk_assign(Xd, consumed.to(DEV), min_dist=True)
+    # update alone on the generating labels
+    C_u, lp_u, n_u = fk.fk_update(Xd, lab.to(DEV), C0.to(DEV))
+    # two iterations in one call
+    C = C0.to(DEV).clone()
+    a2, n2, lp2 = fk.fk_lloyd_iter(Xd, C, 2)
+    C1 = C0.to(DEV).clone()
+    a1, n1, lp1 = fk.fk_lloyd_iter(Xd, C1, 1)
+    torch.cuda.synchronize()
+    assert torch.equal(Xd, keep)
+    assert C_u.shape == (B, K, d) and lp2.shape == (B, K, d)
+    assert torch.equal(lp_u.cpu(), C_u.cpu().to(dtype)) and torch.equal(lp2.cpu(), C.cpu().to(dtype))
+    tol = parity.CENTROID_TOL[dtype]
+    for b in range(B):
+        Xb = parity.widen(X[b])
+        ref = oracle.assign(Xb, parity.widen(consumed[b]))
+        parity.check_assign(Xb, parity.widen(consumed[b]), a[b].cpu().numpy(), ref)
+        same = a[b].cpu().numpy() == ref["assign"]
+        scale = ref["xnorm2"] + (parity.widen(consumed[b]).astype(np.float64) ** 2).sum(1)[a[b].cpu().numpy()]
+        bound = (1e-3 if dtype != torch.float32 else 1e-5) * scale + 1e-6
+        assert (np.abs(md[b].cpu().numpy()[same] - ref["best"][same]) <= bound[same]).all()
+        parity.check_update(Xb, lab[b].numpy(), C0[b].numpy(), C_u[b].cpu().numpy(), n_u[b].cpu().numpy(), tol)
+        # first iteration of the iterating call, then the second on top of it
+        assert torch.equal(a1[b], a[b])
+        parity.check_update(Xb, a1[b].cpu().numpy(), C0[b].numpy(), C1[b].cpu().numpy(), n1[b].cpu().numpy(), tol)
+        parity.check_assign(Xb, parity.widen(lp1[b].cpu()), a2[b].cpu().numpy())
+        parity.check_update(Xb, a2[b].cpu().numpy(), C1[b].cpu().numpy(), C[b].cpu().numpy(), n2[b].cpu().numpy(), tol)
+
+
+def test_out_of_core_needs_a_multiple_of_8():
+    assert fk.fk_ooc_workspace_bytes(4096, 100, 16, torch.float16) == 0
 
 
 # ---------------------------------------------------------------------------------------
