@@ -34,6 +34,8 @@
  *     which fk_workspace_bytes includes) and copy the centroids back without the padding.
  *     fk_lloyd_ooc and the fk_standard_* comparators need d to be a multiple of 8.  Anything
  *     else returns FK_EUNSUPPORTED or FK_EINVAL; there is no fallback path.
+ *   - One device per process: kernel attributes and occupancy are queried once, on the device
+ *     that is current at the first call of a shape class, and remembered.
  *   - Every function returns an fk_status; on failure fk_last_error() holds a message for
  *     the calling thread.  Nothing throws or aborts.
  */
