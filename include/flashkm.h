@@ -31,9 +31,10 @@
  *     The kernels work on rows whose width is a multiple of 8; for any other d the in-core
  *     entry points first copy X and C into zero-padded rows inside the workspace (zeros change
  *     no distance and no mean; costs one extra pass over X per call and room for the copy,
- *     which fk_workspace_bytes includes) and copy the centroids back without the padding.
- *     fk_lloyd_ooc and the fk_standard_* comparators need d to be a multiple of 8.  Anything
- *     else returns FK_EUNSUPPORTED or FK_EINVAL; there is no fallback path.
+ *     which fk_workspace_bytes includes) and copy the centroids back without the padding;
+ *     fk_lloyd_ooc lands the host rows in padded chunk buffers with a pitched copy instead.
+ *     The fk_standard_* comparators need d to be a multiple of 8.  Anything else returns
+ *     FK_EUNSUPPORTED or FK_EINVAL; there is no fallback path.
  *   - One device per process: kernel attributes and occupancy are queried once, on the device
  *     that is current at the first call of a shape class, and remembered.
  *   - Every function returns an fk_status; on failure fk_last_error() holds a message for

@@ -21,8 +21,9 @@ struct OocLayout {
 
 static bool ooc_layout(int64_t chunk_rows, int d, int K, fk_dtype t, OocLayout* L, Geometry* g) {
     if (!make_geometry(1, chunk_rows, d, K, t, g)) return false;
-    if (g->d != g->d_user) return false;   // chunks are consumed as they arrive: no padded copy here
-    L->chunk_bytes = align_up((size_t)chunk_rows * d * elem_size(t), 256);
+    // chunk buffers hold rows of the kernels' width (a multiple of 8); narrower host rows land in
+    // them through a pitched copy, the padding columns are zeroed once
+    L->chunk_bytes = align_up((size_t)chunk_rows * g->d * elem_size(t), 256);
     L->core_bytes = align_up(carve(*g, nullptr).bytes, 256);
     L->assign_bytes = align_up((size_t)chunk_rows * 4, 256);
     L->total = 2 * L->chunk_bytes + L->core_bytes + L->assign_bytes;
@@ -90,8 +91,11 @@ fk_status fk_lloyd_ooc(const void* X_host, float* C_f32, int32_t* assign, int32_
     void* core = base + 2 * L.chunk_bytes;
     int32_t* chunk_assign = (int32_t*)(base + 2 * L.chunk_bytes + L.core_bytes);
     const Workspace wfull = carve(gfull, core);
-    const size_t row_bytes = (size_t)d * elem_size(t);
+    const size_t row_bytes = (size_t)d * elem_size(t);                 // a row on the host
+    const size_t dev_row_bytes = (size_t)gfull.d * elem_size(t);       // a row in a chunk buffer
+    const bool pad = gfull.d != gfull.d_user;
     const int64_t nchunks = cdiv(N, chunk_rows);
+    float* const C_user = C_f32;
 
     hipStream_t cs = (hipStream_t)stream;
     hipStream_t side = nullptr;
@@ -130,6 +134,11 @@ fk_status fk_lloyd_ooc(const void* X_host, float* C_f32, int32_t* assign, int32_
         OOC_HIP(hipEventCreateWithFlags(&freed[i], hipEventDisableTiming));
     }
     bool used[2] = {false, false};
+    if (pad) {
+        OOC_HIP(hipMemsetAsync(xbuf[0], 0, 2 * L.chunk_bytes, side));
+        OOC_TRY(launch_copy_rows(C_user, wfull.c_pad_f32, K, gfull.d_user, gfull.d, 4, cs));
+        C_f32 = wfull.c_pad_f32;
+    }
 
     for (int it = 0; it < iters; ++it) {
         OOC_TRY(launch_round_centroids(gfull, C_f32, t == FK_F32 ? nullptr : wfull.c_lp,
@@ -140,8 +149,12 @@ fk_status fk_lloyd_ooc(const void* X_host, float* C_f32, int32_t* assign, int32_
             const int64_t rows = (N - r0) < chunk_rows ? (N - r0) : chunk_rows;
             // side stream: refill buffer bi once its previous consumer is done
             if (used[bi]) OOC_HIP(hipStreamWaitEvent(side, freed[bi], 0));
-            OOC_HIP(hipMemcpyAsync(xbuf[bi], (const char*)X_host + (size_t)r0 * row_bytes,
-                                   (size_t)rows * row_bytes, hipMemcpyHostToDevice, side));
+            if (pad)
+                OOC_HIP(hipMemcpy2DAsync(xbuf[bi], dev_row_bytes, (const char*)X_host + (size_t)r0 * row_bytes,
+                                         row_bytes, row_bytes, (size_t)rows, hipMemcpyHostToDevice, side));
+            else
+                OOC_HIP(hipMemcpyAsync(xbuf[bi], (const char*)X_host + (size_t)r0 * row_bytes,
+                                       (size_t)rows * row_bytes, hipMemcpyHostToDevice, side));
             OOC_HIP(hipEventRecord(ready[bi], side));
             // compute stream
             OOC_HIP(hipStreamWaitEvent(cs, ready[bi], 0));
@@ -174,6 +187,7 @@ fk_status fk_lloyd_ooc(const void* X_host, float* C_f32, int32_t* assign, int32_
             used[bi] = true;
         }
     }
+    if (pad) OOC_TRY(launch_copy_rows(C_f32, C_user, K, gfull.d, gfull.d_user, 4, cs));
     OOC_HIP(hipStreamSynchronize(side));
     OOC_HIP(hipStreamSynchronize(cs));
     cleanup();

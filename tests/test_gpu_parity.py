@@ -303,6 +303,9 @@ def test_lloyd_multi_iteration_call_equals_repeated_single_calls():
     (torch.float32, 20000, 32, 20, 20000),        # single chunk
     (torch.bfloat16, 30000, 128, 64, 0),          # chunk size chosen from the workspace
     (torch.float16, 20000, 256, 100, 8192),       # wide features
+    (torch.float16, 30000, 100, 50, 8192),        # rows that are not a multiple of 8 wide: pitched copies
+    (torch.float32, 9000, 5, 7, 4096),
+    (torch.bfloat16, 10000, 3, 4, 0),
 ])
 def test_out_of_core_equals_in_core(dtype, N, d, K, chunk):
     w, X, _, C0 = _problem(dtype, 1, N, d, K, seed=300 + N)
@@ -511,10 +514,6 @@ def test_any_row_width(dtype, B, N, d, K):
         parity.check_update(Xb, a1[b].cpu().numpy(), C0[b].numpy(), C1[b].cpu().numpy(), n1[b].cpu().numpy(), tol)
         parity.check_assign(Xb, parity.widen(lp1[b].cpu()), a2[b].cpu().numpy())
         parity.check_update(Xb, a2[b].cpu().numpy(), C1[b].cpu().numpy(), C[b].cpu().numpy(), n2[b].cpu().numpy(), tol)
-
-
-def test_out_of_core_needs_a_multiple_of_8():
-    assert fk.fk_ooc_workspace_bytes(4096, 100, 16, torch.float16) == 0
 
 
 # ---------------------------------------------------------------------------------------
