@@ -448,8 +448,8 @@ __global__ __launch_bounds__(WAVES * 64) void assign_mfma_wide_kernel(
 // workgroup, then every wave walks its own sequence of 32-point batches with no further
 // barrier.  A batch is copied global -> LDS (direct, no registers) with every load
 // instruction covering whole contiguous rows -- the MFMA operand pattern itself would touch
-// each 128-byte line four times with 32 bytes used per touch -- into one of two wave-private
-// LDS buffers, the next batch being requested before the current one is computed; the
+// each 128-byte line four times with 32 bytes used per touch -- into a wave-private ring of
+// three LDS buffers (two batches in flight while a third is computed); the
 // fragments are then read back from LDS.  The 16-byte pieces of a row are stored XOR-swizzled
 // by the row number so that those reads are free of bank conflicts.  Same scores, packing and
 // tie rules as the sweeping kernel above.
@@ -467,7 +467,7 @@ __global__ __launch_bounds__(WAVES * 64) void assign_mfma_stream_kernel(
     __shared__ float sbias[KT * 32];
     extern __shared__ uintx4 dyn_lds[];                // per wave: a ring of 3 batch buffers
     const int ppr = d >> 3;                            // 16-byte pieces per row
-    constexpr int loads = DCH;                         // load instructions per batch (some may be empty)
+    constexpr int loads = DCH;                         // copy instructions per batch, always all issued
     const int swz = (ppr & (ppr - 1)) == 0 ? min(ppr, 8) - 1 : 0;   // XOR mask for the piece index
 
     const int b = blockIdx.y;
