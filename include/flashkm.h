@@ -84,6 +84,25 @@ fk_status fk_assign(const void* X, const void* C, int32_t* assign, float* min_di
                     void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * fk_assign for callers that cannot allocate device memory and have no workspace to hand over:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels and results as fk_assign, minus ws / ws_bytes: the fragment-ordered
+ * centroid copy and the score bias go into a static device array inside the library
+ * (16.25 MiB per GPU that uses the library, held until the process ends) instead of the
+ * caller's workspace.  The call allocates and frees nothing.
+ *   Limits: d a multiple of 8; for FK_F16 / FK_BF16
+ *           B * ceil(K/32) * c(d) KiB <= fk_assign_static_limit() = 16 MiB, c(d) = 2, 4, 8, 16, 32
+ *           for d <= 32, 64, 128, 256, 512 (K = 65536 at d = 128 with B = 1 just fits), and
+ *           B * ceil(K/32) <= 2048.  Beyond that: FK_EWORKSPACE (d not a multiple of 8:
+ *           FK_EUNSUPPORTED).  FK_F32 needs no scratch and has no limit of its own.
+ *   Every call on a GPU shares that GPU's array and rewrites the part it needs before reading
+ *   it; two calls that overlap in time on one GPU (different streams or threads) race.
+ */
+fk_status fk_assign_static(const void* X, const void* C, int32_t* assign, float* min_dist,
+                           int B, int64_t N, int d, int K, fk_dtype t, void* stream);
+size_t fk_assign_static_limit(void);
+
+/*
  * Inverse mapping of Section 4.2 (Algorithm 3, first two lines): stable argsort of the
  * assignment vector by cluster id.
  *   assign      device, [B,N] int32 with values in [0,K)  (values outside are undefined

@@ -22,7 +22,7 @@ _STATUS = {0: "FK_OK", 1: "FK_EINVAL", 2: "FK_EUNSUPPORTED", 3: "FK_EWORKSPACE",
 EXPORTS = ("fk_last_error", "fk_workspace_bytes", "fk_assign", "fk_sort_inverse", "fk_update",
            "fk_lloyd_iter", "fk_lloyd_ooc", "fk_ooc_workspace_bytes", "fk_stage_timer_start",
            "fk_stage_timer_stop", "fk_plan", "fk_set_option", "fk_standard_assign",
-           "fk_standard_update")
+           "fk_standard_update", "fk_assign_static", "fk_assign_static_limit")
 STAGES = ("assign", "sort", "reduce", "finalize")
 
 
@@ -53,6 +53,10 @@ def lib() -> ctypes.CDLL:
         L.fk_ooc_workspace_bytes.argtypes = [i64, i32, i32, i32]
         L.fk_assign.restype = i32
         L.fk_assign.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, vp, sz, vp]
+        L.fk_assign_static.restype = i32
+        L.fk_assign_static.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, vp]
+        L.fk_assign_static_limit.restype = sz
+        L.fk_assign_static_limit.argtypes = []
         L.fk_sort_inverse.restype = i32
         L.fk_sort_inverse.argtypes = [vp, vp, vp, i32, i64, i32, vp, sz, vp]
         L.fk_update.restype = i32
@@ -133,6 +137,19 @@ def fk_assign(X, C, *, min_dist: bool = False, ws=None, out=None):
     md = torch.empty((B, N), dtype=torch.float32, device=X.device) if min_dist else None
     _check(lib().fk_assign(_ptr(X), _ptr(C), _ptr(a), _ptr(md), B, N, d, K, _DTYPE[X.dtype],
                            _ptr(ws), ws.numel(), _stream(X.device)))
+    return (a, md) if min_dist else a
+
+
+def fk_assign_static(X, C, *, min_dist: bool = False, out=None):
+    """fk_assign without a workspace: the library's static scratch holds the centroid layout.
+    The outputs are the caller's (allocated here when not passed in)."""
+    B, N, d, K = _shape3(X, C)
+    _dev(X, "X"); _dev(C, "C", X.dtype)
+    a = out if out is not None else torch.empty((B, N), dtype=torch.int32, device=X.device)
+    _dev(a, "out", torch.int32, (B, N))
+    md = torch.empty((B, N), dtype=torch.float32, device=X.device) if min_dist else None
+    _check(lib().fk_assign_static(_ptr(X), _ptr(C), _ptr(a), _ptr(md), B, N, d, K,
+                                  _DTYPE[X.dtype], _stream(X.device)))
     return (a, md) if min_dist else a
 
 

@@ -5,6 +5,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 #include "fk_common.h"
@@ -248,6 +249,42 @@ static fk_status run_update(const Geometry& g, const Workspace& w, const void* X
     return FK_OK;
 }
 
+// ---------------------------------------------------------------- static scratch
+// Scratch of the allocation-free entry point fk_assign_static: the fragment-ordered centroid
+// copy followed by the score bias.  The array lives in the code object (every GPU that loads
+// the library holds its own copy until the process ends); in host code its name is only a
+// handle for hipGetSymbolAddress, never an address to hand to a kernel.
+constexpr size_t kStaticFragBytes = (size_t)16 << 20;    // B * ceil(K/32) * dchunks KiB
+constexpr size_t kStaticBiasBytes = (size_t)256 << 10;   // B * ceil(K/32) * 32 floats
+static __device__ __align__(256) __attribute__((used)) unsigned char
+    scratch[kStaticFragBytes + kStaticBiasBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices] = {};            // device address of `scratch`, per device
+
+// Device address of the static scratch on the current device (looked up once per device).
+static fk_status static_scratch(unsigned char** out) {
+    int dev = 0;
+    FK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) {
+        set_error("fk_assign_static: device ordinal %d out of range (0..%d)", dev, kMaxDevices - 1);
+        return FK_EUNSUPPORTED;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        FK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || ((uintptr_t)p & 255u)) {
+            set_error("fk_assign_static: static scratch has no usable device address");
+            return FK_EHIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = (unsigned char*)g_scratch_ptr[dev];
+    return FK_OK;
+}
+
 }  // namespace fk
 
 using namespace fk;
@@ -379,6 +416,51 @@ fk_status fk_assign(const void* X, const void* C, int32_t* assign, float* min_di
     if (t == FK_F32) return launch_assign(g, X, C, nullptr, assign, min_dist, s);
     FK_TRY(launch_prepare_centroids(g, C, w.c_frag, w.c_bias, s));
     return launch_assign(g, X, w.c_frag, w.c_bias, assign, min_dist, s);
+}
+
+size_t fk_assign_static_limit(void) { return kStaticFragBytes; }
+
+fk_status fk_assign_static(const void* X, const void* C, int32_t* assign, float* min_dist, int B,
+                           int64_t N, int d, int K, fk_dtype t, void* stream) {
+    const char* fn = "fk_assign_static";
+    if (B < 1 || N < 1 || K < 1 || d < 1) {
+        set_error("%s: B, N, d, K must be positive (B=%d N=%lld d=%d K=%d)", fn, B, (long long)N, d, K);
+        return FK_EINVAL;
+    }
+    if (t != FK_F32 && t != FK_F16 && t != FK_BF16) {
+        set_error("%s: unknown dtype %d", fn, (int)t);
+        return FK_EINVAL;
+    }
+    Geometry g;
+    if (!make_geometry(B, N, d, K, t, &g)) {
+        set_error("%s: unsupported shape B=%d N=%lld d=%d K=%d", fn, B, (long long)N, d, K);
+        return FK_EUNSUPPORTED;
+    }
+    if (g.d != g.d_user) {
+        set_error("%s: d must be a multiple of 8 (a padded copy of X would not fit the static scratch)", fn);
+        return FK_EUNSUPPORTED;
+    }
+    FK_REQUIRE_PTR(fn, X);
+    FK_REQUIRE_PTR(fn, C);
+    FK_REQUIRE_PTR(fn, assign);
+    FK_OPTIONAL_PTR(fn, min_dist);
+    hipStream_t s = (hipStream_t)stream;
+    if (t == FK_F32) return launch_assign(g, X, C, nullptr, assign, min_dist, s);   // no scratch at all
+    const size_t frag_bytes = (size_t)B * g.ktiles * g.dchunks * 64 * 16;
+    const size_t bias_bytes = (size_t)B * g.ktiles * 32 * 4;
+    if (frag_bytes > kStaticFragBytes || bias_bytes > kStaticBiasBytes) {
+        set_error("%s: centroids too large for the static scratch: B*ceil(K/32)*%d KiB = %zu bytes, limit %zu",
+                  fn, g.dchunks, frag_bytes, kStaticFragBytes);
+        return FK_EWORKSPACE;
+    }
+    unsigned char* base = nullptr;
+    FK_TRY(static_scratch(&base));
+    void* c_frag = base;
+    float* c_bias = (float*)(base + kStaticFragBytes);
+    // both regions are rewritten in full for this shape before the assign kernel reads them, so
+    // nothing left by an earlier call is ever read
+    FK_TRY(launch_prepare_centroids(g, C, c_frag, c_bias, s));
+    return launch_assign(g, X, c_frag, c_bias, assign, min_dist, s);
 }
 
 fk_status fk_sort_inverse(const int32_t* assign, int32_t* sorted_idx, int32_t* seg_offsets,
