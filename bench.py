@@ -48,6 +48,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--repeats", type=int, default=7,
+                    help="timed blocks of --steps iterations; the median block is reported")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="default workload only: leave out the short runs of the other in-core "
+                         "configurations (other_configs in the JSON line)")
     ap.add_argument("--sweep-variants", action="store_true",
                     help="time the assign kernel's tile shapes exhaustively over a grid of shapes "
                          "and compare with the shape heuristic's pick (prints one JSON line)")
@@ -109,7 +114,34 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
-    # ---------------------------------------------------------------- inputs (synthetic)
+    out = measure(w, steps, args.warmup, args.repeats, torch, fk, wl, dev,
+                  cpu=not args.no_cpu_baseline)
+    if args.workload == "c2" and not args.no_other_configs:
+        # the other in-core configurations, each at its own iteration count (short: < 1 s each)
+        others = {}
+        for ow in (wl.C1, wl.C3, wl.C4):
+            r = measure(ow, ow.iters, args.warmup, max(5, min(args.repeats, 7)), torch, fk, wl, dev, cpu=False)
+            others[ow.name] = {k: r[k] for k in ("config", "steps", "repeats", "ms_per_step", "ms_per_step_min",
+                                                 "ms_per_step_max", "value", "dtype", "roofline",
+                                                 "kernel_ms", "stage_interval_ms") if k in r}
+            for k in ("assign_tflops", "update_gbps", "update_frac_of_hbm_peak", "fused_pass_gbps"):
+                if k in r:
+                    others[ow.name][k] = r[k]
+        out["other_configs"] = others
+    print(json.dumps(out))
+    return 0
+
+
+def _median(v):
+    v = sorted(v)
+    n = len(v)
+    return v[n // 2] if n % 2 else 0.5 * (v[n // 2 - 1] + v[n // 2])
+
+
+def measure(w, steps, warmup, repeats, torch, fk, wl, dev, cpu=True):
+    """One in-core configuration: throughput (median of `repeats` blocks of `steps` iterations,
+    each block between a HIP event pair on the kernels' stream), per-stage event intervals, and
+    kernel-only durations of the big kernels (stage timer with back-to-back repeats)."""
     X, lab = wl.make_points(w, device=dev, return_labels=True)
     idx = wl.init_rows(w, lab if w.zipf_s > 0 else None)
     C0 = wl.gather_rows(X, idx).contiguous()
@@ -126,129 +158,130 @@ def main() -> int:
     # ---------------------------------------------------------------- throughput
     # The part leaves its idle clock only under sustained load (1.2 GHz idle; the first tens of
     # milliseconds of work run below the clock it then holds), so the device is first kept busy
-    # for ~0.2 s with the same iteration, untimed, and the centroids are put back; the W warm-up
-    # steps and the K timed steps then see the steady state a long run sees.
+    # for ~0.2 s with the same iteration, untimed; every timed block then starts from the initial
+    # centroids, runs W untimed warm-up steps and K timed steps between two events recorded on
+    # the stream the kernels run on (torch's current stream), with a device synchronisation on
+    # both sides.  The median block is the reported figure.
     t_pre = time.perf_counter()
     prewarm = 0
     while time.perf_counter() - t_pre < 0.2:
         run(10)
         torch.cuda.synchronize()
         prewarm += 10
-    C.copy_(C0)
-    if args.warmup > 0:
-        run(args.warmup)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run(steps)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / steps
-    assert int(counts.sum()) == w.B * w.N
+    block_ms, host_ms = [], []
+    for _ in range(max(1, repeats)):
+        C.copy_(C0)
+        if warmup > 0:
+            run(warmup)
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        run(steps)
+        e1.record()
+        torch.cuda.synchronize()
+        host_ms.append((time.perf_counter() - t0) * 1e3 / steps)
+        block_ms.append(e0.elapsed_time(e1) / steps)
+        assert int(counts.sum()) == w.B * w.N
+    ms_per_step = _median(block_ms)
 
-    # ---------------------------------------------------------------- per-stage (instrumented rerun)
-    C.copy_(C0)
-    if args.warmup > 0:
-        run(args.warmup)
-    torch.cuda.synchronize()
-    fk.fk_stage_timer_start()
-    run(steps)
-    stages = fk.fk_stage_timer_stop()
-    avg = {k: (v[0] / v[1] if v[1] else 0.0) for k, v in stages.items()}   # ms per iteration
+    # ---------------------------------------------------------------- per-stage (instrumented reruns)
+    def staged(repeat):
+        C.copy_(C0)
+        if warmup > 0:
+            run(warmup)
+        torch.cuda.synchronize()
+        fk.fk_set_option("timer_repeat", repeat)
+        fk.fk_stage_timer_start()
+        run(steps)
+        st = fk.fk_stage_timer_stop()
+        fk.fk_set_option("timer_repeat", 1)
+        return {k: (v[0] / v[1] if v[1] else 0.0) for k, v in st.items()}   # ms per launch
+
+    interval = staged(1)          # one launch between two events: over-reads the kernel
+    kernel = staged(8)            # eight launches back to back per interval: the kernel's own time
 
     es = 4 if w.dtype == "fp32" else 2
     flops = 2.0 * w.B * w.N * w.K * w.d
-    fused = "stream_update" in fk.fk_plan(w.B, w.N, w.d, w.K, w.torch_dtype)
-    if fused:
-        return report_fused(args, w, steps, ms_per_step, avg, es, flops, X, C0, torch, prewarm)
-    assign_tflops = flops / (avg["assign"] * 1e-3) / 1e12
-    assign_bytes = w.B * (w.N * w.d * es + w.K * w.d * es + 4 * w.K + 4 * w.N)
-    upd_bytes = w.B * (w.N * (w.d * es + 12) + w.K * w.d * (4 + es))
-    upd_ms = avg["sort"] + avg["reduce"] + avg["finalize"]
-    update_gbps = upd_bytes / (upd_ms * 1e-3) / 1e9
-
-    # dominant kernel: the assignment kernel wherever its contraction outweighs streaming X
-    # (K above the MFMA/HBM ridge of ~312 flop/byte); otherwise the update's row gather
-    if w.dtype != "fp32" and w.K >= 312:
-        roof = {"kernel": "assign_mfma_kernel", "bound": "mfma", "achieved": assign_tflops,
-                "peak": PEAK_MFMA_F16_TFLOPS, "unit": "TFLOP/s",
-                "frac": assign_tflops / PEAK_MFMA_F16_TFLOPS,
-                "traffic": _traffic_from_profiles("assign_mfma_kernel", w.name),
-                "avg_launch_ms": avg["assign"]}
-    elif w.dtype == "fp32":
-        # 3 fp32 VALU flops (sub, mul, add) per (point, centroid, feature)
-        t = 1.5 * flops / (avg["assign"] * 1e-3) / 1e12
-        roof = {"kernel": "assign_f32_kernel", "bound": "alu", "achieved": t,
-                "peak": PEAK_FP32_VALU_TFLOPS, "unit": "TFLOP/s",
-                "frac": t / PEAK_FP32_VALU_TFLOPS, "traffic": None,
-                "avg_launch_ms": avg["assign"]}
-    else:
-        # few centroids: both big kernels stream X; the row gather of the update is reported
-        red_bytes = w.B * (w.N * (w.d * es + 4))
-        g = red_bytes / (avg["reduce"] * 1e-3) / 1e9
-        roof = {"kernel": "segment_reduce_kernel", "bound": "hbm", "achieved": g,
-                "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": g / PEAK_HBM_GBPS,
-                "traffic": _traffic_from_profiles("segment_reduce_kernel", w.name),
-                "avg_launch_ms": avg["reduce"]}
-
+    plan = fk.fk_plan(w.B, w.N, w.d, w.K, w.torch_dtype)
+    fused = "stream_update" in plan or "table_update" in plan
     out = {
         "metric": "lloyd_iterations_per_s",
         "value": 1e3 / ms_per_step,
         "unit": "iterations/s",
-        "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step,
+        "repeats": len(block_ms),
+        "ms_per_step_min": min(block_ms), "ms_per_step_max": max(block_ms),
+        "ms_per_step_host_clock_median": _median(host_ms),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {"fp16": "f16", "bf16": "bf16", "fp32": "f32"}[w.dtype],
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "N": w.N, "d": w.d, "K": w.K,
                    "storage": w.dtype, "accumulate": "f32"},
-        "assign_tflops": assign_tflops,
-        "assign_frac_of_mfma_peak": assign_tflops / PEAK_MFMA_F16_TFLOPS,
-        "assign_gbps": assign_bytes / (avg["assign"] * 1e-3) / 1e9,
-        "update_gbps": update_gbps,
-        "update_frac_of_hbm_peak": update_gbps / PEAK_HBM_GBPS,
-        "stage_ms": avg,
-        "roofline": roof,
+        "plan": plan,
+        "kernel_ms": kernel,
+        "stage_interval_ms": interval,
         "prewarm_iterations_untimed": prewarm,
     }
-
-    # ---------------------------------------------------------------- CPU oracle baseline
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, X, C0, torch)
-    print(json.dumps(out))
-    return 0
-
-
-def report_fused(args, w, steps, ms_per_step, avg, es, flops, X, C0, torch, prewarm):
-    """Few clusters: assignment and sums come out of ONE streaming pass over X (the stage timer
-    books it under "assign"; there is no sort and no gather), followed by the merge/normalise.
-    The pass is HBM-bound; its algorithmic bytes are X and C read once and the assignment
-    written once."""
     pass_bytes = w.B * (w.N * w.d * es + w.K * w.d * es + 4 * w.K + 4 * w.N)
-    g = pass_bytes / (avg["assign"] * 1e-3) / 1e9
-    out = {
-        "metric": "lloyd_iterations_per_s",
-        "value": 1e3 / ms_per_step,
-        "unit": "iterations/s",
-        "n_gpus": 1, "steps": steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": {"fp16": "f16", "bf16": "bf16"}[w.dtype],
-        "data": "synthetic",
-        "config": {"workload": w.name, "B": w.B, "N": w.N, "d": w.d, "K": w.K,
-                   "storage": w.dtype, "accumulate": "f32", "update": "fused one-hot MFMA pass"},
-        "assign_tflops": flops / (avg["assign"] * 1e-3) / 1e12,
-        "fused_pass_gbps": g,
-        "stage_ms": avg,
-        "roofline": {"kernel": "stream_update_kernel", "bound": "hbm", "achieved": g,
-                     "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": g / PEAK_HBM_GBPS,
-                     "traffic": _traffic_from_profiles("stream_update_kernel", w.name),
-                     "avg_launch_ms": avg["assign"]},
-        "prewarm_iterations_untimed": prewarm,
-    }
-    if not args.no_cpu_baseline:
+    if fused:
+        # assignment and sums come out of ONE streaming pass over X (booked under "assign"; no
+        # sort, no gather), followed by the merge/normalise.  HBM-bound: X and C read once, the
+        # assignment written once.
+        kname = "table_update_kernel" if "table_update" in plan else "stream_update_kernel"
+        g = pass_bytes / (kernel["assign"] * 1e-3) / 1e9
+        out["config"]["update"] = "fused into the assignment pass (one-hot MFMA table)"
+        out["assign_tflops"] = flops / (kernel["assign"] * 1e-3) / 1e12
+        out["fused_pass_gbps"] = g
+        out["roofline"] = _roof(kname, "hbm", g, PEAK_HBM_GBPS, "GB/s", w, kernel["assign"], interval["assign"])
+    else:
+        assign_tflops = flops / (kernel["assign"] * 1e-3) / 1e12
+        upd_bytes = w.B * (w.N * (w.d * es + 12) + w.K * w.d * (4 + es))
+        upd_ms = kernel["sort"] + kernel["reduce"] + kernel["finalize"]
+        update_gbps = upd_bytes / (upd_ms * 1e-3) / 1e9
+        out.update({
+            "assign_tflops": assign_tflops,
+            "assign_frac_of_mfma_peak": assign_tflops / PEAK_MFMA_F16_TFLOPS,
+            "assign_gbps": pass_bytes / (kernel["assign"] * 1e-3) / 1e9,
+            "update_gbps": update_gbps,
+            "update_frac_of_hbm_peak": update_gbps / PEAK_HBM_GBPS,
+            "update_ms": upd_ms,
+        })
+        # dominant kernel: the assignment kernel wherever its contraction outweighs streaming X
+        # (K above the MFMA/HBM ridge of ~312 flop/byte); otherwise the update's row gather
+        if w.dtype != "fp32" and w.K >= 312:
+            out["roofline"] = _roof("assign_mfma_kernel", "mfma", assign_tflops, PEAK_MFMA_F16_TFLOPS,
+                                    "TFLOP/s", w, kernel["assign"], interval["assign"])
+        elif w.dtype == "fp32":
+            # 3 fp32 VALU flops (sub, mul, add) per (point, centroid, feature)
+            t = 1.5 * flops / (kernel["assign"] * 1e-3) / 1e12
+            out["roofline"] = _roof("assign_f32_kernel", "alu", t, PEAK_FP32_VALU_TFLOPS, "TFLOP/s", w,
+                                    kernel["assign"], interval["assign"])
+        else:
+            # few centroids: both big kernels stream X; the row gather of the update is reported
+            red_bytes = w.B * (w.N * (w.d * es + 4))
+            g = red_bytes / (kernel["reduce"] * 1e-3) / 1e9
+            out["roofline"] = _roof("segment_reduce_kernel", "hbm", g, PEAK_HBM_GBPS, "GB/s", w,
+                                    kernel["reduce"], interval["reduce"])
+    if cpu:
         out["cpu_baseline"] = cpu_baseline(w, X, C0, torch)
-    print(json.dumps(out))
-    return 0
+    del X, ws, assign
+    torch.cuda.empty_cache()
+    return out
+
+
+def _roof(kname, bound, achieved, peak, unit, w, kernel_ms, interval_ms):
+    """Roofline entry of the dominant kernel.  `achieved` uses the kernel's own mean duration
+    (back-to-back launches between one event pair, live in this run); the single-launch event
+    interval, which also holds the events' own cost, is kept beside it.  `traffic` is not measured
+    in this run: it is the figure of the committed rocprofv3 --pmc summary, when there is one."""
+    return {"kernel": kname, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+            "frac": achieved / peak, "avg_launch_ms": kernel_ms,
+            "avg_launch_ms_single_event_interval": interval_ms,
+            "traffic": _traffic_from_profiles(kname, w.name),
+            "traffic_source": f"profiles/{kname}_{w.name}_traffic.txt (offline rocprofv3 --pmc run)"}
 
 
 def _time_us(torch, fn, reps=5):
@@ -475,20 +508,11 @@ def bench_ooc(args, w, steps, torch, fk, wl, dev):
     Xh = torch.empty((1, w.N, w.d), dtype=w.torch_dtype, pin_memory=True)
     print(f"pinned {Xh.numel() * 2 / 2**30:.1f} GiB in {time.perf_counter() - t0:.1f} s",
           file=sys.stderr, flush=True)
-    # workloads.make_points generates on the GPU block by block and copies each block down
-    g = torch.Generator(device=dev)
-    g.manual_seed(w.seed)
-    centres = torch.randn((w.K, w.d), generator=g, device=dev) * w.center_std
-    blk = 1 << 24
-    for r0 in range(0, w.N, blk):
-        r1 = min(w.N, r0 + blk)
-        lab = torch.randint(0, w.K, (r1 - r0,), generator=g, device=dev)
-        x = torch.randn((r1 - r0, w.d), generator=g, device=dev).mul_(w.noise_std).add_(centres[lab])
-        Xh[0, r0:r1].copy_(x.to(w.torch_dtype))
-        del x, lab
+    # generated on the GPU block by block, each block copied down into the pinned buffer
+    wl.make_points(w, device=dev, rows_per_block=1 << 24, out=Xh)
     print(f"generated in {time.perf_counter() - t0:.1f} s", file=sys.stderr, flush=True)
-    idx = torch.randint(0, w.N, (w.K,), generator=torch.Generator().manual_seed(w.seed + 1000))
-    C = Xh[0][idx].to(torch.float32).to(dev).contiguous()
+    idx = wl.init_rows(w)
+    C = Xh[0][idx[0]].to(torch.float32).to(dev).contiguous()
     C0 = C.clone()
     chunk = min(1 << 24, w.N)
     need = fk.fk_ooc_workspace_bytes(chunk, w.d, w.K, w.torch_dtype)

@@ -207,6 +207,10 @@ fk_status fk_standard_update(const void* X, const int32_t* assign, const float* 
  *   "sort_min_rounds" r  sort workgroups own at least r sub-tiles of 4096 keys (the rule gives
  *                        one up to 2^24 keys); changes fk_workspace_bytes, so set it before sizing
  *   "fused_update"   0   few clusters: do not take the sort-free update below
+ *   "timer_repeat"   r   measurement only: while the stage timer runs, the assignment (or fused)
+ *                        kernel and the segment reduction are each launched r times back to back
+ *                        inside their interval (same outputs rewritten), so that interval /
+ *                        launches approaches the kernel's own duration
  * Few clusters (FK_F16 / FK_BF16, K <= 32, d <= 128): fk_lloyd_iter computes assignment and
  * per-workgroup tables of sums in ONE pass over X (a one-hot MFMA adds each 32-point batch into
  * the K x d table; Section 4.2's on-chip partial sums with no sort needed), and fk_update
@@ -221,8 +225,8 @@ int fk_set_option(const char* name, int value);
  * record a HIP event on their stream after each stage of every iteration -- assignment
  * kernel, sort-inverse, segment reduction, merge/normalise (with the centroid re-layout).
  * fk_stage_timer_stop waits for the last event and returns, per stage in that order,
- * the summed elapsed milliseconds and the number of intervals in stage_ms[4] /
- * stage_launches[4] (host arrays); its return value is the number of events recorded, or -1
+ * the summed elapsed milliseconds and the number of kernel launches timed (one per interval
+ * unless "timer_repeat" is set) in stage_ms[4] / stage_launches[4] (host arrays); its return value is the number of events recorded, or -1
  * on a HIP error.  One recorder per process, not thread safe; the events add a few
  * microseconds per stage, so throughput is measured with the timer stopped.
  */

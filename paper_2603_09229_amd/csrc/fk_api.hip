@@ -35,10 +35,19 @@ struct StageTimer {
     std::vector<hipEvent_t> pool;     // events owned by the recorder, reused across runs
     size_t used = 0;
     std::vector<int> stage;           // stage closed by mark i (-1 = opens an iteration)
+    std::vector<int> launches;        // kernel launches of that stage inside the interval
+    int repeat = 1;                   // fk_set_option("timer_repeat")
 };
 static StageTimer g_timer;
 
-static void timer_mark(hipStream_t s, int stage) {
+// While the recorder runs, the two bandwidth- or MFMA-sized kernels of an iteration (assignment
+// or fused pass; segment reduction) are launched this many times back to back inside their
+// interval: they only read their inputs and rewrite the same outputs, so the result does not
+// change, and interval / launches then approaches the kernel's own duration (the events' cost
+// is paid once per interval).
+static int timer_repeat() { return g_timer.on ? g_timer.repeat : 1; }
+
+static void timer_mark(hipStream_t s, int stage, int launches = 1) {
     if (!g_timer.on) return;
     if (g_timer.used == g_timer.pool.size()) {
         hipEvent_t e;
@@ -47,6 +56,7 @@ static void timer_mark(hipStream_t s, int stage) {
     }
     if (hipEventRecord(g_timer.pool[g_timer.used], s) != hipSuccess) { g_timer.on = false; return; }
     g_timer.stage.push_back(stage);
+    g_timer.launches.push_back(launches);
     ++g_timer.used;
 }
 
@@ -227,8 +237,9 @@ static fk_status run_stream_update(const Geometry& g, const Workspace& w, const 
                                    int32_t* assign, bool compute_assign, const FinalizeArgs& fa,
                                    hipStream_t s) {
     int G = 0;
-    FK_TRY(launch_stream_update(g, w, X, assign, compute_assign, &G, s));
-    timer_mark(s, compute_assign ? kStageAssign : kStageReduce);
+    const int rep = timer_repeat();
+    for (int r = 0; r < rep; ++r) FK_TRY(launch_stream_update(g, w, X, assign, compute_assign, &G, s));
+    timer_mark(s, compute_assign ? kStageAssign : kStageReduce, rep);
     Geometry gm = g;
     gm.max_items = (int64_t)g.K * G;       // partial rows per instance as that pass wrote them
     FK_TRY(launch_finalize(gm, w, nullptr, nullptr, fa, s, w.wg_counts, G));
@@ -242,8 +253,10 @@ static fk_status run_update(const Geometry& g, const Workspace& w, const void* X
     if (fused_update_enabled(g)) return run_stream_update(g, w, X, (int32_t*)assign, false, fa, s);
     FK_TRY(launch_sort_inverse(g, w, assign, w.sorted_idx, w.seg_off, w.item_off, s));
     timer_mark(s, kStageSort);
-    FK_TRY(launch_segment_reduce(g, w, X, w.sorted_idx, w.seg_off, w.item_off, s));
-    timer_mark(s, kStageReduce);
+    const int rep = timer_repeat();
+    for (int r = 0; r < rep; ++r)
+        FK_TRY(launch_segment_reduce(g, w, X, w.sorted_idx, w.seg_off, w.item_off, s));
+    timer_mark(s, kStageReduce, rep);
     FK_TRY(launch_finalize(g, w, w.seg_off, w.item_off, fa, s));
     timer_mark(s, kStageFinalize);
     return FK_OK;
@@ -296,6 +309,7 @@ const char* fk_last_error(void) { return fk::g_err; }
 void fk_stage_timer_start(void) {
     g_timer.used = 0;
     g_timer.stage.clear();
+    g_timer.launches.clear();
     g_timer.on = true;
 }
 
@@ -314,11 +328,12 @@ int fk_stage_timer_stop(double* stage_ms, int* stage_launches) {
         if (hipEventElapsedTime(&ms, g_timer.pool[i - 1], g_timer.pool[i]) != hipSuccess) return -1;
         if (relayout) { stage_ms[kStageFinalize] += ms; continue; }
         stage_ms[st] += ms;
-        stage_launches[st] += 1;
+        stage_launches[st] += g_timer.launches[i];
     }
     const int n = (int)g_timer.used;
     g_timer.used = 0;             // a later stop without a start reports nothing
     g_timer.stage.clear();
+    g_timer.launches.clear();
     return n;
 }
 
@@ -337,6 +352,10 @@ int fk_set_option(const char* name, int value) {
     }
     if (name && strcmp(name, "sort_stage_bins") == 0 && value >= -1 && value <= 2048) {
         set_sort_stage_bins(value);
+        return FK_OK;
+    }
+    if (name && strcmp(name, "timer_repeat") == 0 && value >= -1 && value <= 64) {
+        g_timer.repeat = value < 1 ? 1 : value;
         return FK_OK;
     }
     if (name && strcmp(name, "fused_update") == 0 && value >= -1 && value <= 1) {
@@ -605,11 +624,14 @@ fk_status fk_lloyd_iter(const void* X, float* C_f32, void* C_lp, int32_t* assign
         // few clusters: assignment and sums in one pass over X (see run_stream_update)
         const bool fused = fused_update_enabled(g);
         if (!fused) {
-            if (t == FK_F32)
-                FK_TRY(launch_assign(g, X, C_f32, nullptr, assign, nullptr, s));
-            else
-                FK_TRY(launch_assign(g, X, w.c_frag, w.c_bias, assign, nullptr, s));
-            timer_mark(s, kStageAssign);
+            const int rep = timer_repeat();
+            for (int r = 0; r < rep; ++r) {
+                if (t == FK_F32)
+                    FK_TRY(launch_assign(g, X, C_f32, nullptr, assign, nullptr, s));
+                else
+                    FK_TRY(launch_assign(g, X, w.c_frag, w.c_bias, assign, nullptr, s));
+            }
+            timer_mark(s, kStageAssign, rep);
         }
         FinalizeArgs fa;
         fa.C_prev_f32 = C_f32;
