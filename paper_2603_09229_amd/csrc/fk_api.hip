@@ -117,6 +117,10 @@ bool make_geometry(int B, int64_t N, int d_user, int K, fk_dtype t, Geometry* g)
     g->fused_grid_cap = 0;
     if (t != FK_F32 && K <= 32 && d <= 128)
         g->fused_grid_cap = (int)std::min<int64_t>(B >= 1024 ? 1 : 1024 / B, cdiv(cdiv(N, 32), 4));
+    // one persistent workgroup per compute unit at most (256 on this part), 256-point batches
+    g->table_grid_cap = 0;
+    if (t != FK_F32 && K > 32 && K <= 256 && d <= 128)
+        g->table_grid_cap = (int)std::min<int64_t>(B >= 256 ? 1 : 256 / B, cdiv(N, 256));
     return true;
 }
 
@@ -152,9 +156,9 @@ Workspace carve(const Geometry& g, void* base) {
         w.c_frag = take((size_t)g.B * g.ktiles * g.dchunks * 64 * 16);
         w.c_bias = (float*)take((size_t)g.B * g.ktiles * 32 * 4);
     }
-    const size_t fused_rows = (size_t)g.K * g.fused_grid_cap;
+    const size_t fused_rows = (size_t)g.K * std::max(g.fused_grid_cap, g.table_grid_cap);
     w.partial = (float*)take((size_t)g.B * std::max((size_t)g.max_items, fused_rows) * g.d * 4);
-    if (g.fused_grid_cap > 0) w.wg_counts = (int32_t*)take((size_t)g.B * fused_rows * 4);
+    if (fused_rows > 0) w.wg_counts = (int32_t*)take((size_t)g.B * fused_rows * 4);
     w.sums = (float*)take(BKd * 4);
     if (g.d != g.d_user) {
         w.x_pad = take(BN * g.d * elem_size(g.t));
@@ -238,7 +242,12 @@ static fk_status run_stream_update(const Geometry& g, const Workspace& w, const 
                                    hipStream_t s) {
     int G = 0;
     const int rep = timer_repeat();
-    for (int r = 0; r < rep; ++r) FK_TRY(launch_stream_update(g, w, X, assign, compute_assign, &G, s));
+    for (int r = 0; r < rep; ++r) {
+        if (g.fused_grid_cap > 0)
+            FK_TRY(launch_stream_update(g, w, X, assign, compute_assign, &G, s));
+        else
+            FK_TRY(launch_table_update(g, w, X, assign, &G, s));    // always computes the assignment
+    }
     timer_mark(s, compute_assign ? kStageAssign : kStageReduce, rep);
     Geometry gm = g;
     gm.max_items = (int64_t)g.K * G;       // partial rows per instance as that pass wrote them
@@ -388,19 +397,25 @@ int fk_plan(int B, int64_t N, int d, int K, fk_dtype t, char* buf, size_t buf_by
         const int v = choose_assign_variant((int64_t)B * N);
         snprintf(assign, sizeof(assign), "mfma_sweep(variant=%d,points_per_wg=%d)", v, pts[v]);
     }
-    if (fused_update_enabled(g)) {
+    if (table_update_enabled(g)) {
+        snprintf(buf, buf_bytes,
+                 "assign+update=table_update(K x d table in the registers of a workgroup, X read once "
+                 "per iteration, no sort; at most %d workgroups per instance) fk_assign alone=%s "
+                 "fk_update alone=sort-inverse workspace=%zu",
+                 g.table_grid_cap, assign, carve(g, nullptr).bytes);
+    } else if (fused_update_enabled(g)) {
         snprintf(buf, buf_bytes,
                  "assign+update=stream_update(one-hot MFMA, X read once per iteration, no sort; "
                  "at most %d workgroups per instance) fk_assign alone=%s workspace=%zu",
                  g.fused_grid_cap, assign, carve(g, nullptr).bytes);
-        return FK_OK;
+    } else {
+        snprintf(buf, buf_bytes,
+                 "assign=%s ktiles=%d sort=%dpass(tile=%d,blocks=%d) reduce=%s(rows_per_item=%d) "
+                 "max_items=%lld workspace=%zu",
+                 assign, g.ktiles, g.sort_passes, g.sort_tile, g.sort_blocks,
+                 g.waves_per_item == 4 ? "workgroup_per_item" : "wave_per_item", g.rows_per_item,
+                 (long long)g.max_items, carve(g, nullptr).bytes);
     }
-    snprintf(buf, buf_bytes,
-             "assign=%s ktiles=%d sort=%dpass(tile=%d,blocks=%d) reduce=%s(rows_per_item=%d) "
-             "max_items=%lld workspace=%zu",
-             assign, g.ktiles, g.sort_passes, g.sort_tile, g.sort_blocks,
-             g.waves_per_item == 4 ? "workgroup_per_item" : "wave_per_item", g.rows_per_item,
-             (long long)g.max_items, carve(g, nullptr).bytes);
     if (g.d != g.d_user) {
         const size_t n = strlen(buf);
         if (n + 1 < buf_bytes) snprintf(buf + n, buf_bytes - n, " rows_padded=%d->%d", g.d_user, g.d);
@@ -622,7 +637,7 @@ fk_status fk_lloyd_iter(const void* X, float* C_f32, void* C_lp, int32_t* assign
     for (int it = 0; it < iters; ++it) {
         timer_mark(s, -1);
         // few clusters: assignment and sums in one pass over X (see run_stream_update)
-        const bool fused = fused_update_enabled(g);
+        const bool fused = fused_update_enabled(g) || table_update_enabled(g);
         if (!fused) {
             const int rep = timer_repeat();
             for (int r = 0; r < rep; ++r) {

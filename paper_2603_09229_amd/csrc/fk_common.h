@@ -63,6 +63,9 @@ struct Geometry {
     // sort-free update for few clusters (16-bit storage, K <= 32, d <= 128): most workgroups
     // per instance it may use, 0 when the shape is not eligible
     int fused_grid_cap;
+    // one-pass update with the K x d table split over the registers of a workgroup (16-bit
+    // storage, 32 < K <= 256, d <= 128): most workgroups per instance, 0 when not eligible
+    int table_grid_cap;
 };
 
 // Carved device workspace (all pointers 256-byte aligned inside the caller's buffer).
@@ -147,6 +150,14 @@ fk_status launch_stream_update(const Geometry& g, const Workspace& w, const void
                                hipStream_t s);
 bool fused_update_enabled(const Geometry& g);
 void set_fused_update_option(int v);       // 0 = never, otherwise whenever the shape allows
+bool fused_update_allowed();               // the option above is not 0
+
+// Up to 256 clusters: assignment and sums in one pass over X with the table of sums in the
+// registers of a persistent workgroup (see fk_table.hip).  Computes and writes the assignment;
+// leaves w.partial / w.wg_counts as launch_stream_update does.
+fk_status launch_table_update(const Geometry& g, const Workspace& w, const void* X,
+                              int32_t* assign, int* grid_out, hipStream_t s);
+bool table_update_enabled(const Geometry& g);
 
 // Row re-layout for widths that are not a multiple of 8: dst[r][j] = j < d_src ? src[r][j] : 0
 // for j < d_dst (padding, d_dst > d_src) or dst[r][j] = src[r][j] for j < d_dst (un-padding,

@@ -261,6 +261,8 @@ static int g_fused_option = -1;   // -1 / 1: use when the shape allows, 0: never
 
 void set_fused_update_option(int v) { g_fused_option = v; }
 
+bool fused_update_allowed() { return g_fused_option != 0; }
+
 bool fused_update_enabled(const Geometry& g) { return g.fused_grid_cap > 0 && g_fused_option != 0; }
 
 template <bool BF, int DCH, bool ASSIGN>

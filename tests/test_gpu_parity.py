@@ -351,7 +351,7 @@ def test_bad_arguments_are_errors_not_crashes():
 
 
 def test_stage_timer_reports_every_stage():
-    w = wl.C2.scaled(N=30000, K=128)
+    w = wl.C2.scaled(N=30000, K=300)                 # general path: all four stages run
     X = wl.make_points(w).to(DEV)
     C = wl.gather_rows(X.cpu(), wl.init_rows(w)).to(DEV)
     fk.fk_stage_timer_start()
@@ -363,6 +363,24 @@ def test_stage_timer_reports_every_stage():
     # stopped: further calls record nothing
     fk.fk_lloyd_iter(X, C, 1)
     assert all(v == (0.0, 0) for v in fk.fk_stage_timer_stop().values())
+    # back-to-back repeats inside an interval: the same results, more launches per interval
+    C1, C2 = C.clone(), C.clone()
+    a1, n1, _ = fk.fk_lloyd_iter(X, C1, 2)
+    fk.fk_set_option("timer_repeat", 4)
+    fk.fk_stage_timer_start()
+    a2, n2, _ = fk.fk_lloyd_iter(X, C2, 2)
+    st = fk.fk_stage_timer_stop()
+    fk.fk_set_option("timer_repeat", 1)
+    assert st["assign"][1] == 8 and st["reduce"][1] == 8 and st["sort"][1] == 2 and st["finalize"][1] == 2
+    assert torch.equal(C1, C2) and torch.equal(a1, a2) and torch.equal(n1, n2)
+    # a fused shape books its single pass under "assign"
+    w = wl.C2.scaled(N=30000, K=128)
+    X = wl.make_points(w).to(DEV)
+    C = wl.gather_rows(X.cpu(), wl.init_rows(w)).to(DEV)
+    fk.fk_stage_timer_start()
+    fk.fk_lloyd_iter(X, C, 3)
+    st = fk.fk_stage_timer_stop()
+    assert st["assign"][1] == 3 and st["finalize"][1] == 3 and st["sort"][1] == 0 and st["reduce"][1] == 0
 
 
 def test_results_do_not_depend_on_the_stream():
@@ -615,6 +633,82 @@ def test_few_cluster_update_clamps_ids_like_the_sort_path(general_path_switch):
     general_path_switch(False)
     assert torch.equal(n_f, n_s)
     parity.check_centroids(C_f[0].cpu().numpy(), C_s[0].cpu().numpy(), 5e-5, "clamped ids")
+
+
+# Up to 256 clusters (16-bit storage, 32 < K <= 256, d <= 128): assignment + table of sums in
+# one pass over X (table split over the registers of a persistent workgroup, compacted one-hot
+# MFMA).  fk_set_option("fused_update", 0) sends the same shape down the general path.
+TABLE_CASES = [
+    # dtype, B, N, d, K, zipf
+    (torch.bfloat16, 4, 32768, 128, 256, 0.0),    # the batched token-clustering recipe, 4 instances
+    (torch.float16, 1, 100001, 128, 256, 0.0),    # ragged last batch, many batches per workgroup
+    (torch.float16, 1, 70000, 64, 200, 1.2),      # skewed: one wave's clusters take most points
+    (torch.bfloat16, 2, 5000, 128, 33, 0.0),      # just above the few-cluster path: waves 2..7 own nothing
+    (torch.float16, 1, 3000, 72, 100, 0.0),       # d not a multiple of 32, no swizzle
+    (torch.float16, 3, 1000, 8, 64, 0.0),         # narrowest row
+    (torch.bfloat16, 1, 255, 32, 40, 0.0),        # less than one batch
+    (torch.float16, 1, 257, 96, 129, 0.0),        # one full batch and one point
+    (torch.float16, 300, 300, 16, 50, 0.0),       # more instances than compute units
+    (torch.bfloat16, 1, 20000, 128, 255, 0.0),    # last cluster row of the last wave unused
+]
+
+
+@pytest.mark.parametrize("dtype,B,N,d,K,zipf", TABLE_CASES)
+def test_table_update_iteration_matches_oracle_and_general_path(dtype, B, N, d, K, zipf, general_path_switch):
+    w, X, lab, C0 = _problem(dtype, B, N, d, K, seed=900 + N + K, zipf=zipf)
+    Xd = X.to(DEV)
+    assert "table_update" in fk.fk_plan(B, N, d, K, dtype)
+    C_f = C0.to(DEV).clone()
+    a_f, n_f, lp_f = fk.fk_lloyd_iter(Xd, C_f, 1)
+    general_path_switch(True)
+    assert "table_update" not in fk.fk_plan(B, N, d, K, dtype)
+    C_s = C0.to(DEV).clone()
+    a_s, n_s, lp_s = fk.fk_lloyd_iter(Xd, C_s, 1)
+    general_path_switch(False)
+    torch.cuda.synchronize()
+    # same scores, same tie rules: identical assignments and counts; sums differ in order only
+    assert torch.equal(a_f, a_s) and torch.equal(n_f, n_s)
+    consumed = C0.to(dtype)
+    for b in range(min(B, 4)):
+        Xb = parity.widen(X[b])
+        parity.check_assign(Xb, parity.widen(consumed[b]), a_f[b].cpu().numpy())
+        parity.check_update(Xb, a_f[b].cpu().numpy(), C0[b].numpy(), C_f[b].cpu().numpy(),
+                            n_f[b].cpu().numpy(), parity.CENTROID_TOL[dtype])
+    for b in range(B):
+        parity.check_centroids(C_f[b].cpu().numpy(), C_s[b].cpu().numpy(), 5e-5, "table vs sort-inverse")
+    assert torch.equal(lp_f.cpu(), C_f.cpu().to(dtype))
+
+
+def test_table_update_all_points_in_one_cluster_and_empty_clusters():
+    """Degenerate membership: every point goes to one cluster (one wave's list holds whole
+    batches, every other cluster stays empty and keeps its centroid)."""
+    dtype, B, N, d, K = torch.float16, 1, 3000, 64, 96
+    g = torch.Generator().manual_seed(5)
+    X = (torch.randn((B, N, d), generator=g) * 0.1 + 3.0).to(dtype)
+    C0 = torch.randn((B, K, d), generator=g) * 50.0
+    C0[0, 70] = 3.0                                # the only centroid near the data
+    C = C0.to(DEV).clone()
+    a, n, _ = fk.fk_lloyd_iter(X.to(DEV), C, 1)
+    assert int(n[0, 70]) == N and int(n.sum()) == N and bool((a == 70).all())
+    parity.check_update(parity.widen(X[0]), a[0].cpu().numpy(), C0[0].numpy(), C[0].cpu().numpy(),
+                        n[0].cpu().numpy(), parity.CENTROID_TOL[dtype])
+
+
+def test_table_update_is_bit_reproducible_and_multi_iteration():
+    w = wl.C3.scaled(B=3, N=20001)
+    X = wl.make_points(w)
+    Xd = X.to(DEV)
+    C0 = wl.gather_rows(X, wl.init_rows(w)).to(DEV)
+    assert "table_update" in fk.fk_plan(w.B, w.N, w.d, w.K, w.torch_dtype)
+    Ca, Cb = C0.clone(), C0.clone()
+    a1, n1, lp1 = fk.fk_lloyd_iter(Xd, Ca, 4)
+    for _ in range(4):
+        a2, n2, lp2 = fk.fk_lloyd_iter(Xd, Cb, 1)
+    assert torch.equal(Ca, Cb) and torch.equal(a1, a2) and torch.equal(n1, n2) and torch.equal(lp1, lp2)
+    assert int(n1.sum()) == w.B * w.N
+    Cc = C0.clone()
+    a3, _, _ = fk.fk_lloyd_iter(Xd, Cc, 1)
+    assert torch.equal(a3, fk.fk_assign(Xd, C0.to(w.torch_dtype)))
 
 
 def test_kernel_choices_do_not_change_the_result():
