@@ -278,10 +278,10 @@ fk_status launch_finalize(const Geometry& g, const Workspace& w, const int32_t* 
     if (lp32 == a.C_out_f32) lp32 = nullptr;
     uint16_t* frag = g.t == FK_F32 ? nullptr : (uint16_t*)a.c_frag;
     // few clusters with many partial rows each: more rows in flight per workgroup
-    // ... and many clusters with one or two rows each: the smallest workgroup that still has a
-    // thread per feature
+    // ... and many clusters with few rows each (up to 4, or up to 8 when there are thousands of
+    // clusters to spread over the chip): the smallest workgroup that still has a thread per feature
     int threads = g.max_items / g.K > 64 ? 1024 : 256;
-    if (g.max_items / g.K <= 4 && g.d <= 128) threads = 64;
+    if (g.d <= 128 && (g.max_items / g.K <= 4 || (g.max_items / g.K <= 8 && (int64_t)g.K * g.B >= 4096))) threads = 64;
     const size_t lds = ((size_t)4 * threads + g.d) * sizeof(float);
     hipLaunchKernelGGL(finalize_kernel, dim3(g.K, g.B), dim3(threads), lds, s, w.partial, seg_off,
                        item_off, a.C_prev_f32, a.C_out_f32, lp16, lp32, frag, a.c_bias, a.counts,
