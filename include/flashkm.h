@@ -18,9 +18,15 @@
  *     `ws` buffer of at least fk_workspace_bytes(...) bytes (256-byte aligned), whose
  *     contents are undefined before and after a call.
  *   - X is never written.
- *   - Indices are 0-based int32 (the paper counts from 1).  Ties in the argmin go to the
- *     lowest index among the scores the kernel computes (fp32); a cluster with no member
- *     keeps its previous centroid.
+ *   - Indices are 0-based int32 (the paper counts from 1).  Ties in the argmin: FK_F32 takes
+ *     the lowest index among equal fp32 distances.  FK_F16 / FK_BF16 compare fp32 scores
+ *     x.c - |c|^2/2 truncated to 19 mantissa bits; among centroids whose truncated scores are
+ *     equal the lowest index wins, with one exception: inside a tile of 32 consecutive
+ *     centroids (k / 32 equal) and among those of its rows that agree in bit 2 of k (one lane's
+ *     16 rows), a NEGATIVE winning score (a point nearer the origin than any centroid) goes to
+ *     the highest row instead.  Either way the chosen centroid's score is within 2^-19 relative
+ *     of the best one, far inside the tolerance the parity tests allow.
+ *     A cluster with no member keeps its previous centroid.
  *   - Inputs must be finite; for FK_F16 twice the largest centroid norm must stay finite
  *     in fp32 (always true for fp16 data).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
@@ -50,7 +56,14 @@
 extern "C" {
 #endif
 
+/* Storage type of X and of the low-precision centroids.  An int in the ABI: any other value is
+ * answered with FK_EINVAL (in C++ the underlying type is fixed so that such a value is still a
+ * valid object to pass and test). */
+#ifdef __cplusplus
+typedef enum : int { FK_F32 = 0, FK_F16 = 1, FK_BF16 = 2 } fk_dtype;
+#else
 typedef enum { FK_F32 = 0, FK_F16 = 1, FK_BF16 = 2 } fk_dtype;
+#endif
 
 typedef enum {
     FK_OK = 0,
@@ -149,7 +162,8 @@ fk_status fk_lloyd_iter(const void* X, float* C_f32, void* C_lp, int32_t* assign
 
 /*
  * Out-of-core Lloyd iterations (Section 4.3, chunked stream overlap), B = 1.
- *   X_host     PINNED host memory, [N,d] of dtype t.  Chunks of `chunk_rows` rows are
+ *   X_host     PINNED host memory, [N,d] of dtype t (hipHostMalloc; anything else, pageable
+ *              memory included, is refused with FK_EINVAL).  Chunks of `chunk_rows` rows are
  *              copied with hipMemcpyAsync on a side stream owned by the call into two
  *              device buffers carved from dev_ws while the previous chunk is assigned and
  *              reduced on `stream`.

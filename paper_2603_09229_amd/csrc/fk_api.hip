@@ -124,7 +124,7 @@ bool make_geometry(int B, int64_t N, int d_user, int K, fk_dtype t, Geometry* g)
     return true;
 }
 
-Workspace carve(const Geometry& g, void* base) {
+Workspace carve(const Geometry& g, void* base, bool padded_x) {
     Workspace w;
     memset(&w, 0, sizeof(w));
     size_t off = 0;
@@ -161,7 +161,7 @@ Workspace carve(const Geometry& g, void* base) {
     if (fused_rows > 0) w.wg_counts = (int32_t*)take((size_t)g.B * fused_rows * 4);
     w.sums = (float*)take(BKd * 4);
     if (g.d != g.d_user) {
-        w.x_pad = take(BN * g.d * elem_size(g.t));
+        if (padded_x) w.x_pad = take(BN * g.d * elem_size(g.t));
         w.c_pad_f32 = (float*)take(BKd * 4);
         w.c_pad_lp = take(BKd * elem_size(g.t));
     }

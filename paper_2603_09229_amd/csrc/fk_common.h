@@ -91,8 +91,9 @@ struct Workspace {
 };
 
 bool make_geometry(int B, int64_t N, int d, int K, fk_dtype t, Geometry* g);
-// Lays the workspace out from `base` (may be NULL to only compute the size).
-Workspace carve(const Geometry& g, void* base);
+// Lays the workspace out from `base` (may be NULL to only compute the size).  padded_x = false
+// leaves out the zero-padded copy of X (the out-of-core call pads through its pitched copies).
+Workspace carve(const Geometry& g, void* base, bool padded_x = true);
 
 // ---------------------------------------------------------------- kernel launchers
 // Each enqueues on `s` and returns FK_OK / FK_EHIP.  Pointers are device pointers.

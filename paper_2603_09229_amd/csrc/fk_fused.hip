@@ -119,43 +119,66 @@ __global__ __launch_bounds__(WAVES * 64) void stream_update_kernel(
 
         // LDS reads through opaque instructions: the wait for the copy that filled this buffer
         // was issued by hand, and the compiler must not add one for the younger copy in flight.
+        // Every group of reads sits in ONE asm statement together with its wait, with all its
+        // results as outputs: no result register can be touched between issue and arrival.
         uintx4 xf[ASSIGN ? DCH : 1];
         if (ASSIGN) {
+            uint32_t xa[DCH];
 #pragma unroll
             for (int s = 0; s < DCH; ++s) {
                 const int piece = min(2 * s + h, ppr - 1);       // chunks past d meet zero centroid features
-                asm volatile("ds_read_b128 %0, %1" : "=v"(xf[s]) : "v"(lds_addr(bufc + n * ppr + (piece ^ (n & swz)))) : "memory");
+                xa[s] = lds_addr(bufc + n * ppr + (piece ^ (n & swz)));
+            }
+            if constexpr (DCH == 2)
+                asm volatile("ds_read_b128 %0, %2\n\tds_read_b128 %1, %3\n\ts_waitcnt lgkmcnt(0)"
+                             : "=&v"(xf[0]), "=&v"(xf[1]) : "v"(xa[0]), "v"(xa[1]) : "memory");
+            else if constexpr (DCH == 4)
+                asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %5\n\tds_read_b128 %2, %6\n\t"
+                             "ds_read_b128 %3, %7\n\ts_waitcnt lgkmcnt(0)"
+                             : "=&v"(xf[0]), "=&v"(xf[1]), "=&v"(xf[2]), "=&v"(xf[3])
+                             : "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3]) : "memory");
+            else {
+                static_assert(DCH == 2 || DCH == 4 || DCH == 8, "feature chunks per point");
+                asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %5\n\tds_read_b128 %2, %6\n\t"
+                             "ds_read_b128 %3, %7\n\ts_waitcnt lgkmcnt(0)"
+                             : "=&v"(xf[0]), "=&v"(xf[1]), "=&v"(xf[2]), "=&v"(xf[3])
+                             : "v"(xa[0]), "v"(xa[1]), "v"(xa[2]), "v"(xa[3]) : "memory");
+                asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %5\n\tds_read_b128 %2, %6\n\t"
+                             "ds_read_b128 %3, %7\n\ts_waitcnt lgkmcnt(0)"
+                             : "=&v"(xf[4 % DCH]), "=&v"(xf[5 % DCH]), "=&v"(xf[6 % DCH]), "=&v"(xf[7 % DCH])
+                             : "v"(xa[4 % DCH]), "v"(xa[5 % DCH]), "v"(xa[6 % DCH]), "v"(xa[7 % DCH]) : "memory");
             }
         }
+        // transposed operand: one statement (four reads + wait) per (half batch, column block)
         uintx2 xt[2][CB][2];
 #pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2)
+        for (int s2 = 0; s2 < 2; ++s2) {
+            uint32_t ta[CB][2];
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     const int row = 16 * s2 + 8 * h + 4 * u + (L >> 2);
-                    const uint32_t a = lds_addr(bufc + row * ppr + (tr_piece[cb] ^ (row & swz))) + ((L & 1) << 3);
-                    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(xt[s2][cb][u]) : "v"(a) : "memory");
+                    ta[cb][u] = lds_addr(bufc + row * ppr + (tr_piece[cb] ^ (row & swz))) + ((L & 1) << 3);
                 }
+#pragma unroll
+            for (int cb = 0; cb + 1 < CB || cb == 0; cb += 2) {
+                if (cb + 1 < CB)
+                    asm volatile("ds_read_b64_tr_b16 %0, %4\n\tds_read_b64_tr_b16 %1, %5\n\t"
+                                 "ds_read_b64_tr_b16 %2, %6\n\tds_read_b64_tr_b16 %3, %7\n\ts_waitcnt lgkmcnt(0)"
+                                 : "=&v"(xt[s2][cb][0]), "=&v"(xt[s2][cb][1]), "=&v"(xt[s2][(cb + 1) % CB][0]),
+                                   "=&v"(xt[s2][(cb + 1) % CB][1])
+                                 : "v"(ta[cb][0]), "v"(ta[cb][1]), "v"(ta[(cb + 1) % CB][0]), "v"(ta[(cb + 1) % CB][1])
+                                 : "memory");
+                else
+                    asm volatile("ds_read_b64_tr_b16 %0, %2\n\tds_read_b64_tr_b16 %1, %3\n\ts_waitcnt lgkmcnt(0)"
+                                 : "=&v"(xt[s2][cb][0]), "=&v"(xt[s2][cb][1]) : "v"(ta[cb][0]), "v"(ta[cb][1]) : "memory");
+            }
+        }
         int k = 0;
         if (!ASSIGN)
-            asm volatile("ds_read_b32 %0, %1" : "=v"(k) : "v"(lds_addr(bufc + DCH * 64) + (uint32_t)(n << 2)) : "memory");
-        // one wait for all of them; naming the registers afterwards keeps their uses behind it
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-            for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-                for (int u = 0; u < 2; ++u) asm volatile("" : "+v"(xt[s2][cb][u]));
-        if (ASSIGN) {
-#pragma unroll
-            for (int s = 0; s < DCH; ++s) asm volatile("" : "+v"(xf[s]));
-        } else {
-            asm volatile("" : "+v"(k));
-        }
+            asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)"
+                         : "=&v"(k) : "v"(lds_addr(bufc + DCH * 64) + (uint32_t)(n << 2)) : "memory");
 
         const bool issued = t2 < nbatches;
         if (issued) request(t2, buf2);

@@ -24,7 +24,7 @@ static bool ooc_layout(int64_t chunk_rows, int d, int K, fk_dtype t, OocLayout* 
     // chunk buffers hold rows of the kernels' width (a multiple of 8); narrower host rows land in
     // them through a pitched copy, the padding columns are zeroed once
     L->chunk_bytes = align_up((size_t)chunk_rows * g->d * elem_size(t), 256);
-    L->core_bytes = align_up(carve(*g, nullptr).bytes, 256);
+    L->core_bytes = align_up(carve(*g, nullptr, false).bytes, 256);
     L->assign_bytes = align_up((size_t)chunk_rows * 4, 256);
     L->total = 2 * L->chunk_bytes + L->core_bytes + L->assign_bytes;
     return true;
@@ -55,6 +55,28 @@ fk_status fk_lloyd_ooc(const void* X_host, float* C_f32, int32_t* assign, int32_
         ((uintptr_t)X_host & 15u)) {
         set_error("fk_lloyd_ooc: NULL or misaligned pointer");
         return FK_EINVAL;
+    }
+    {
+        // X_host must be pinned (page-locked) host memory: from pageable memory hipMemcpyAsync
+        // stages through a bounce buffer and the copies no longer overlap the kernels.  Both ends
+        // of the array are looked up.
+        const size_t bytes = (size_t)N * (size_t)d * elem_size(t);
+        const char* ends[2] = {(const char*)X_host, (const char*)X_host + (bytes ? bytes - 1 : 0)};
+        for (const char* p : ends) {
+            hipPointerAttribute_t attr;
+            const hipError_t pe = hipPointerGetAttributes(&attr, p);
+            if (pe != hipSuccess) {
+                (void)hipGetLastError();      // an unknown pointer is reported as an error: clear it
+                set_error("fk_lloyd_ooc: X_host is not pinned host memory (the HIP runtime does not know the pointer: %s)",
+                          hipGetErrorString(pe));
+                return FK_EINVAL;
+            }
+            if (attr.type != hipMemoryTypeHost) {
+                set_error("fk_lloyd_ooc: X_host must be pinned host memory (hipHostMalloc), got memory type %d",
+                          (int)attr.type);
+                return FK_EINVAL;
+            }
+        }
     }
     Geometry gfull;
     OocLayout L;
@@ -90,7 +112,7 @@ fk_status fk_lloyd_ooc(const void* X_host, float* C_f32, int32_t* assign, int32_
     void* xbuf[2] = {base, base + L.chunk_bytes};
     void* core = base + 2 * L.chunk_bytes;
     int32_t* chunk_assign = (int32_t*)(base + 2 * L.chunk_bytes + L.core_bytes);
-    const Workspace wfull = carve(gfull, core);
+    const Workspace wfull = carve(gfull, core, false);
     const size_t row_bytes = (size_t)d * elem_size(t);                 // a row on the host
     const size_t dev_row_bytes = (size_t)gfull.d * elem_size(t);       // a row in a chunk buffer
     const bool pad = gfull.d != gfull.d_user;

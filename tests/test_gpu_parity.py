@@ -131,6 +131,39 @@ def test_assign_exact_duplicates_go_to_lowest_index():
     parity.check_assign(parity.widen(X[0]), parity.widen(C[0]), a)
 
 
+def test_assign_duplicates_with_negative_winning_scores_stay_inside_the_tolerance_rule():
+    """Points closer to the origin than to any centroid: every score x.c - |c|^2/2 is negative.
+    Among rows that share a lane of a centroid tile (here rows 0, 1 and 2, 3 of a tile) the kernel
+    then keeps the HIGHER of two exactly equal scores' rows, where Eq. 2's reading is the lowest
+    index; the difference is a zero-gap tie, which the tolerance rule covers, and nothing else
+    may differ."""
+    for dtype in (torch.float16, torch.bfloat16):
+        g = torch.Generator().manual_seed(21)
+        K, d, N = 70, 64, 3000
+        C = (torch.randn((1, K, d), generator=g) * 8.0).to(dtype)
+        for k in (0, 2, 32):        # the three centroids nearest the origin, of about equal norm
+            C[0, k] = (C[0, k].float() * 0.5).to(dtype)
+        C[0, 1] = C[0, 0]           # same lane's rows of tile 0
+        C[0, 3] = C[0, 2]
+        C[0, 33] = C[0, 32]         # and of tile 1
+        X = (torch.randn((1, N, d), generator=g) * 0.05).to(dtype)
+        # make the duplicated centroids the winners for many points: pull a third of the points
+        # a little towards each pair (scores stay negative: |x| << |c|)
+        for j, k in enumerate((0, 2, 32)):
+            X[0, j::3] = (X[0, j::3].float() + 0.02 * C[0, k].float()).to(dtype)
+        a = fk.fk_assign(X.to(DEV), C.to(DEV)).cpu().numpy()[0]
+        Xw, Cw = parity.widen(X[0]), parity.widen(C[0])
+        best_score = (Xw.astype(np.float64) @ Cw.astype(np.float64).T - 0.5 * (Cw.astype(np.float64) ** 2).sum(1)).max(1)
+        assert (best_score < 0).all()
+        st = parity.check_assign(Xw, Cw, a)                       # raises on any unexcused mismatch
+        ref = oracle.assign(Xw, Cw.astype(np.float64))["assign"]
+        diff = a != ref
+        # every difference is a duplicate pair resolved the other way round
+        assert set(zip(ref[diff].tolist(), a[diff].tolist())) <= {(0, 1), (2, 3), (32, 33)}
+        assert st["excused"] == int(diff.sum())
+        assert np.isin(ref, [0, 2, 32]).mean() > 0.5              # the case is really exercised
+
+
 def test_assign_does_not_depend_on_tiling_position():
     """Online argmin: shifting where a point falls in a tile must not change its answer."""
     w, X, _, C0 = _problem(torch.float16, 1, 1500, 64, 200, seed=9)
@@ -348,6 +381,64 @@ def test_bad_arguments_are_errors_not_crashes():
     assert e.value.status == 2          # the comparators take no padded widths
     with pytest.raises(ValueError):
         fk.fk_lloyd_ooc(torch.zeros((64, 16), dtype=torch.float16), C[0].float(), 1, dev_ws=small)
+
+
+def test_out_of_core_refuses_pageable_host_memory():
+    """Through the raw C ABI: the chunk stream only overlaps the kernels from pinned memory, so
+    anything else is an argument error, found on the host before any work is enqueued."""
+    import ctypes
+    L = fk.lib()
+    N, d, K = 5000, 64, 16
+    X = (torch.randn((N, d)) * 3).to(torch.float16)                 # pageable
+    assert not X.is_pinned()
+    C = torch.randn((K, d), device=DEV)
+    counts = torch.zeros((K,), dtype=torch.int32, device=DEV)
+    need = fk.fk_ooc_workspace_bytes(2048, d, K, torch.float16)
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+    vp = ctypes.c_void_p
+    args = lambda x: (vp(x), vp(C.data_ptr()), None, vp(counts.data_ptr()), N, d, K, fk.FK_F16, 1, 2048,
+                      vp(ws.data_ptr()), need, None)
+    C_before = C.clone()
+    rc = L.fk_lloyd_ooc(*args(X.data_ptr()))
+    assert rc == 1 and b"pinned" in L.fk_last_error(), L.fk_last_error()
+    rc = L.fk_lloyd_ooc(*args(ws.data_ptr()))                       # device memory is not host memory either
+    assert rc == 1 and b"pinned" in L.fk_last_error(), L.fk_last_error()
+    torch.cuda.synchronize()
+    assert torch.equal(C, C_before)                                 # nothing ran
+    Xp = X.pin_memory()
+    assert L.fk_lloyd_ooc(*args(Xp.data_ptr())) == 0, L.fk_last_error()
+    assert int(counts.sum()) == N
+
+
+def test_merge_bound_of_the_segment_level_update():
+    """Section 4.2's count of merges: with chunks of R sorted positions at most K + ceil(N/R)
+    partial rows are ever merged.  Here a cluster's run is cut into ceil(n_k/R) items, so the
+    item table must end at or below that bound (read back from the workspace: sorted_idx,
+    seg_off and item_off are its first three arrays, each padded to 256 bytes)."""
+    for (B, N, d, K, zipf) in ((1, 100000, 64, 300, 0.0), (2, 70001, 32, 2000, 1.2), (1, 300000, 16, 5000, 0.0),
+                               (1, 5000000, 8, 40, 1.5)):
+        w, X, lab, C0 = _problem(torch.float16, B, N, d, K, seed=40 + K, zipf=zipf)
+        ws = fk.make_workspace(B, N, d, K, torch.float16, DEV)
+        fk.fk_set_option("fused_update", 0)
+        try:
+            plan = fk.fk_plan(B, N, d, K, torch.float16)
+            fk.fk_update(X.to(DEV), lab.to(DEV), C0.to(DEV), ws=ws)
+        finally:
+            fk.fk_set_option("fused_update", -1)
+        torch.cuda.synchronize()
+        R = int(plan.split("rows_per_item=")[1].split(")")[0])
+        al = lambda v: (v + 255) // 256 * 256
+        o_seg = al(B * N * 4)
+        o_item = o_seg + al(B * (K + 1) * 4)
+        seg = ws[o_seg:o_seg + B * (K + 1) * 4].view(torch.int32).view(B, K + 1).cpu()
+        item = ws[o_item:o_item + B * (K + 1) * 4].view(torch.int32).view(B, K + 1).cpu()
+        for b in range(B):
+            n_k = torch.bincount(lab[b].to(torch.int64), minlength=K)
+            assert torch.equal(seg[b, 1:] - seg[b, :-1], n_k.to(torch.int32))        # the offsets really are these arrays
+            items = (n_k + R - 1) // R
+            assert torch.equal(item[b, 1:] - item[b, :-1], items.to(torch.int32))
+            assert int(item[b, K]) <= K + (N + R - 1) // R, (int(item[b, K]), K, N, R)
+            assert int(item[b, K]) >= (N + R - 1) // R
 
 
 def test_stage_timer_reports_every_stage():
