@@ -41,8 +41,10 @@
  *     fk_lloyd_ooc lands the host rows in padded chunk buffers with a pitched copy instead.
  *     The fk_standard_* comparators need d to be a multiple of 8.  Anything else returns
  *     FK_EUNSUPPORTED or FK_EINVAL; there is no fallback path.
- *   - One device per process: kernel attributes and occupancy are queried once, on the device
- *     that is current at the first call of a shape class, and remembered.
+ *   - Calls act on the device that is current in the calling thread.  Kernel attributes,
+ *     occupancy and the device's sizes (compute units, LDS, last-level cache) are asked of the
+ *     runtime once per device and remembered; the options of fk_set_option are process-wide
+ *     atomics.  The stage timer is the one part that is not thread safe.
  *   - Every function returns an fk_status; on failure fk_last_error() holds a message for
  *     the calling thread.  Nothing throws or aborts.
  */

@@ -22,6 +22,8 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     f"-I{ROOT / 'include'}", f"-I{CSRC}",
 ]
+# the HSA runtime (already a dependency of the HIP runtime) is asked for the cache sizes
+LIBS = ["-L/opt/rocm/lib", "-lhsa-runtime64"]
 
 
 def sources() -> list[Path]:
@@ -31,7 +33,7 @@ def sources() -> list[Path]:
 def build(verbose: bool = True) -> Path:
     """Always recompiles (a few tens of seconds); raises on any compiler error."""
     tmp = LIB.with_suffix(f".tmp{os.getpid()}.so")
-    cmd = [HIPCC, *FLAGS, "-o", str(tmp), *map(str, sources())]
+    cmd = [HIPCC, *FLAGS, "-o", str(tmp), *map(str, sources()), *LIBS]
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, capture_output=True, text=True)

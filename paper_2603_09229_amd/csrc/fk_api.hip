@@ -8,6 +8,8 @@
 #include <mutex>
 #include <vector>
 
+#include <hsa/hsa.h>
+
 #include "fk_common.h"
 
 namespace fk {
@@ -66,7 +68,7 @@ static int ceil_log2(int v) {
     return b;
 }
 
-static int g_sort_min_rounds = 0;   // fk_set_option("sort_min_rounds")
+static std::atomic<int> g_sort_min_rounds{0};   // fk_set_option("sort_min_rounds")
 
 bool make_geometry(int B, int64_t N, int d_user, int K, fk_dtype t, Geometry* g) {
     if (B < 1 || N < 1 || K < 1 || K > 65536 || d_user < 1 || d_user > 512) return false;
@@ -103,7 +105,8 @@ bool make_geometry(int B, int64_t N, int d_user, int K, fk_dtype t, Geometry* g)
     // and no histogram / scan kernel runs)
     // testing aid: larger tiles than the rule would pick (the several-rounds-per-workgroup form
     // of the sort kernels is otherwise only reached beyond 2^24 keys)
-    if (g_sort_min_rounds > 1 && T < (int64_t)4096 * g_sort_min_rounds) T = (int64_t)4096 * g_sort_min_rounds;
+    const int min_rounds = g_sort_min_rounds.load(std::memory_order_relaxed);
+    if (min_rounds > 1 && T < (int64_t)4096 * min_rounds) T = (int64_t)4096 * min_rounds;
     g->sort_tile = (int)T;
     g->sort_blocks = (int)cdiv(N, T);
     // rows reduced into one partial row: 256 by one wave, or, for N above 4M points, N/4096 by
@@ -181,14 +184,75 @@ static size_t sort_workspace_bytes(const Geometry& g) {
     return off;
 }
 
-int device_cu_count() {
-    static int cus = [] {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return 256;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 256;
-        return n > 0 ? n : 256;
-    }();
-    return cus;
+int current_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    return dev >= 0 && dev < kMaxDevices ? dev : 0;
+}
+
+namespace {
+
+// Largest cache of the GPU agent with ordinal `want` (HSA lists L1, L2 and, where there is one,
+// the memory-side last-level cache); 0 if the runtime cannot be asked.
+struct CacheQuery { int want, seen; int64_t best; };
+
+hsa_status_t on_cache(hsa_cache_t cache, void* data) {
+    uint32_t size = 0;                    // this runtime counts in KiB (L2 4096, L3 262144 on MI355X)
+    if (hsa_cache_get_info(cache, HSA_CACHE_INFO_SIZE, &size) == HSA_STATUS_SUCCESS) {
+        auto* q = (CacheQuery*)data;
+        if (((int64_t)size << 10) > q->best) q->best = (int64_t)size << 10;
+    }
+    return HSA_STATUS_SUCCESS;
+}
+
+hsa_status_t on_agent(hsa_agent_t agent, void* data) {
+    hsa_device_type_t type;
+    if (hsa_agent_get_info(agent, HSA_AGENT_INFO_DEVICE, &type) != HSA_STATUS_SUCCESS ||
+        type != HSA_DEVICE_TYPE_GPU)
+        return HSA_STATUS_SUCCESS;
+    auto* q = (CacheQuery*)data;
+    if (q->seen++ == q->want) (void)hsa_agent_iterate_caches(agent, on_cache, data);
+    return HSA_STATUS_SUCCESS;
+}
+
+int64_t largest_cache_bytes(int dev) {
+    if (hsa_init() != HSA_STATUS_SUCCESS) return 0;
+    CacheQuery q{dev, 0, 0};
+    (void)hsa_iterate_agents(on_agent, &q);
+    (void)hsa_shut_down();          // the runtime is reference counted: HIP keeps its own hold
+    return q.best;
+}
+
+}  // namespace
+
+const DeviceInfo& device_info() {
+    static DeviceInfo info[kMaxDevices];
+    static std::atomic<int> known[kMaxDevices];
+    const int dev = current_device();
+    if (!known[dev].load(std::memory_order_acquire)) {
+        static std::mutex mu;
+        std::lock_guard<std::mutex> lock(mu);
+        if (!known[dev].load(std::memory_order_relaxed)) {
+            DeviceInfo d{256, (int64_t)160 << 10, (int64_t)256 << 20};
+            int count = 0, v = 0;
+            if (hipGetDeviceCount(&count) == hipSuccess && count > 0) {
+                if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) d.cus = v;
+                if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) == hipSuccess && v > 0)
+                    d.lds_bytes = v;
+                int64_t llc = largest_cache_bytes(dev);
+                if (llc == 0 && hipDeviceGetAttribute(&v, hipDeviceAttributeL2CacheSize, dev) == hipSuccess && v > 0) llc = v;
+                if (llc > 0) d.llc_bytes = llc;
+            } else {
+                (void)hipGetLastError();
+            }
+            info[dev] = d;
+            known[dev].store(1, std::memory_order_release);
+        }
+    }
+    return info[dev];
 }
 
 static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
@@ -281,7 +345,6 @@ constexpr size_t kStaticBiasBytes = (size_t)256 << 10;   // B * ceil(K/32) * 32 
 static __device__ __align__(256) __attribute__((used)) unsigned char
     scratch[kStaticFragBytes + kStaticBiasBytes];
 
-constexpr int kMaxDevices = 64;
 static std::mutex g_scratch_mutex;
 static void* g_scratch_ptr[kMaxDevices] = {};            // device address of `scratch`, per device
 
@@ -356,7 +419,7 @@ int fk_set_option(const char* name, int value) {
         return FK_OK;
     }
     if (name && strcmp(name, "sort_min_rounds") == 0 && value >= -1 && value <= 64) {
-        g_sort_min_rounds = value;
+        g_sort_min_rounds.store(value, std::memory_order_relaxed);
         return FK_OK;
     }
     if (name && strcmp(name, "sort_stage_bins") == 0 && value >= -1 && value <= 2048) {
@@ -394,7 +457,7 @@ int fk_plan(int B, int64_t N, int d, int K, fk_dtype t, char* buf, size_t buf_by
         snprintf(assign, sizeof(assign), "mfma_stream(tiles=%d)", g.ktiles);
     else {
         static const int pts[4] = {256, 512, 512, 128};
-        const int v = choose_assign_variant((int64_t)B * N);
+        const int v = choose_assign_variant(g);
         snprintf(assign, sizeof(assign), "mfma_sweep(variant=%d,points_per_wg=%d)", v, pts[v]);
     }
     if (table_update_enabled(g)) {
@@ -419,6 +482,13 @@ int fk_plan(int B, int64_t N, int d, int K, fk_dtype t, char* buf, size_t buf_by
     if (g.d != g.d_user) {
         const size_t n = strlen(buf);
         if (n + 1 < buf_bytes) snprintf(buf + n, buf_bytes - n, " rows_padded=%d->%d", g.d_user, g.d);
+    }
+    {
+        const DeviceInfo& di = device_info();
+        const size_t n = strlen(buf);
+        if (n + 1 < buf_bytes)
+            snprintf(buf + n, buf_bytes - n, " device(cus=%d,lds=%lldKiB,llc=%lldMiB)", di.cus,
+                     (long long)(di.lds_bytes >> 10), (long long)(di.llc_bytes >> 20));
     }
     return FK_OK;
 }

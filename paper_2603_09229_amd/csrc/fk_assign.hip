@@ -794,22 +794,35 @@ static fk_status launch_mfma_v(const Geometry& g, const void* X, const void* fra
 //   2 = 2 x 8 (512 points, 2 per CU)                 3 = 1 x 4 (128 points, 4 per CU)
 // g_variant_override >= 0 forces one (fk_set_option / FK_ASSIGN_VARIANT); otherwise it is chosen
 // from the shape and the machine, the counterpart of the paper's cache-aware compile
-// heuristic (Section 4.3): no tuning run, just the CU count and each variant's occupancy.
-static int g_variant_override = [] {
+// heuristic (Section 4.3): no tuning run, just what the runtime reports about the device
+// (compute units, last-level cache) and each variant's occupancy.
+static std::atomic<int> g_variant_override{[] {
     const char* e = getenv("FK_ASSIGN_VARIANT");
     return e ? atoi(e) : -1;
-}();
+}()};
+
+// MFMA flop per HBM byte at which the assignment turns from bandwidth- to compute-bound: the
+// ratio of the part's dense 16-bit MFMA rate to its HBM rate (2.5 PFLOP/s over 8 TB/s).  The
+// kernel does K flop per byte of X, so this is also a number of centroids.
+constexpr int kRidgeCentroids = 312;
 
 // Workgroups run in rounds of (CUs x workgroups per CU).  A variant is scored by how full its
 // rounds are, (W/S) / ceil(W/S) with W workgroups over S slots, times its steady-state
 // efficiency relative to the 512-point shape (bigger workgroups re-use each centroid tile
 // more, measured 1.0 / 0.95 / 0.80).  Few points -> small workgroups so the chip fills at all;
-// awkward point counts -> the shape with the least idle last round.
-int choose_assign_variant(int64_t total_points) {
-    if (g_variant_override >= 0 && g_variant_override <= 3) return g_variant_override;
+// awkward point counts -> the shape with the least idle last round.  Below the ridge with X
+// larger than the last-level cache the kernel waits on HBM, not on the matrix pipe, and the
+// 256-point shape (three workgroups per unit, more loads in flight) is the efficient one
+// instead (measured 8-12% ahead of the 512-point shape there).
+int choose_assign_variant(const Geometry& g) {
+    const int forced = g_variant_override.load(std::memory_order_relaxed);
+    if (forced >= 0 && forced <= 3) return forced;
+    const int64_t total_points = (int64_t)g.B * g.N;
+    const DeviceInfo& di = device_info();
+    const bool hbm_bound = g.K < kRidgeCentroids && total_points * g.d * 2 > di.llc_bytes;
     struct V { int id, points, per_cu; double eff; };
-    static const V cand[3] = {{2, 512, 2, 1.0}, {0, 256, 3, 0.95}, {3, 128, 4, 0.80}};
-    const double cus = device_cu_count();
+    const V cand[3] = {{2, 512, 2, hbm_bound ? 0.90 : 1.0}, {0, 256, 3, hbm_bound ? 1.0 : 0.95}, {3, 128, 4, 0.80}};
+    const double cus = di.cus;
     int best = 2;
     double best_score = -1.0;
     for (const V& v : cand) {
@@ -821,32 +834,34 @@ int choose_assign_variant(int64_t total_points) {
     return best;
 }
 
-void set_assign_variant_override(int v) { g_variant_override = v; }
+void set_assign_variant_override(int v) { g_variant_override.store(v, std::memory_order_relaxed); }
 
 // Streaming kernel or sweeping kernel for few centroids?  Measured on MI355X: with X well
-// beyond the last-level cache (256 MiB) and rows of at least 64 bytes the streaming kernel's
-// continuous copies win by 10-20% while C fits one LDS stage (d = 64: up to 128 centroids,
-// d = 128: up to 64); for cache-sized X, narrow rows, or more centroids the sweeping kernel's
-// bulk prologue loads and two points per lane are as fast or faster.  g_stream_option: -1 = that rule,
-// 0 = never, 1 = whenever the centroids fit one LDS stage (FK_ASSIGN_STREAM sets the start
-// value; fk_set_option("assign_stream", v) changes it).
-static int g_stream_option = [] {
+// beyond the last-level cache and rows of at least 64 bytes the streaming kernel's continuous
+// copies win by 10-20% for up to 64 centroids; for cache-sized X, narrow rows, or more centroids the sweeping kernel's bulk prologue
+// loads and two points per lane are as fast or faster.  "Well beyond" = one and a half times
+// the last-level cache the runtime reports (384 MiB on this part).  g_stream_option: -1 = that
+// rule, 0 = never, 1 = whenever the centroids fit one LDS stage (FK_ASSIGN_STREAM sets the
+// start value; fk_set_option("assign_stream", v) changes it).
+static std::atomic<int> g_stream_option{[] {
     const char* e = getenv("FK_ASSIGN_STREAM");
     return e ? atoi(e) : -1;
-}();
+}()};
 
-void set_assign_stream_option(int v) { g_stream_option = v; }
+void set_assign_stream_option(int v) { g_stream_option.store(v, std::memory_order_relaxed); }
 
 bool assign_uses_stream_kernel(const Geometry& g) {
     if (g.t == FK_F32 || g.dchunks > 8) return false;
     const int st = (16 / g.dchunks) < 8 ? (16 / g.dchunks) : 8;
-    if (g.ktiles > st || g_stream_option == 0) return false;
-    if (g_stream_option > 0) return true;
+    const int opt = g_stream_option.load(std::memory_order_relaxed);
+    if (g.ktiles > st || opt == 0) return false;
+    if (opt > 0) return true;
     const int64_t x_bytes = (int64_t)g.B * g.N * g.d * 2;
-    if (x_bytes < ((int64_t)384 << 20) || g.d <= 32) return false;
-    // rows of 128 or 256 bytes are stored swizzled (conflict-free operand reads): every shape
-    // that fits a stage; other widths: two tiles below 128-byte rows, one above
-    const int limit = (g.d == 64 || g.d == 128) ? st : (g.d < 64 ? 2 : 1);
+    if (x_bytes < device_info().llc_bytes * 3 / 2 || g.d <= 32) return false;
+    // up to two centroid tiles (beyond that the sweeping kernel's two points per lane win back
+    // more than the streaming copies save: measured at d = 64, K = 128); one tile for row widths
+    // above 128 bytes that are not stored swizzled
+    const int limit = (g.d == 64 || g.d == 128 || g.d < 64) ? std::min(st, 2) : 1;
     return g.ktiles <= limit;
 }
 
@@ -863,21 +878,17 @@ static fk_status launch_mfma(const Geometry& g, const void* X, const void* frag,
         const bool one_tile = g.ktiles == 1;
         auto kern = one_tile ? assign_mfma_stream_kernel<BF, DCH, WAVES, 1>
                              : assign_mfma_stream_kernel<BF, DCH, WAVES, ST>;
-        static bool attr_set[2] = {false, false};
-        if (!attr_set[one_tile]) {
+        // set / queried once per kernel and device (also keeps the launch path free of runtime
+        // queries, so that it can be captured into a HIP graph after one eager call)
+        static PerDeviceInt per_cu_cache[2];
+        if (per_cu_cache[one_tile].get() == 0) {
             FK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-            attr_set[one_tile] = true;
-        }
-        // queried once per kernel (also keeps the launch path free of runtime queries, so
-        // that it can be captured into a HIP graph after one eager call)
-        static int per_cu_cache[2] = {0, 0};
-        if (per_cu_cache[one_tile] == 0) {
             int q = 0;
             if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&q, kern, WAVES * 64, lds) != hipSuccess || q < 1)
                 q = 1;
-            per_cu_cache[one_tile] = q;
+            per_cu_cache[one_tile].set(q);
         }
-        const int per_cu = per_cu_cache[one_tile];
+        const int per_cu = per_cu_cache[one_tile].get();
         const int64_t nbatches = cdiv(g.N, 32);
         int64_t wgs = (int64_t)device_cu_count() * per_cu;
         if (wgs > cdiv(nbatches, WAVES)) wgs = cdiv(nbatches, WAVES);
@@ -887,7 +898,7 @@ static fk_status launch_mfma(const Geometry& g, const void* X, const void* frag,
         FK_HIP(hipGetLastError());
         return FK_OK;
     }
-    switch (choose_assign_variant((int64_t)g.B * g.N)) {
+    switch (choose_assign_variant(g)) {
         case 1: return launch_mfma_v<BF, DCH, 4, 4>(g, X, frag, bias, assign, min_dist, s);
         case 0: return launch_mfma_v<BF, DCH, 2, 4>(g, X, frag, bias, assign, min_dist, s);
         case 3: return launch_mfma_v<BF, DCH, 1, 4>(g, X, frag, bias, assign, min_dist, s);

@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "flashkm.h"
 
 namespace fk {
@@ -31,8 +33,27 @@ constexpr int kWave = 64;
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t elem_size(fk_dtype t) { return t == FK_F32 ? 4 : 2; }
-// Compute units of the current device (queried once; 256 if the query fails or no GPU is there).
-int device_cu_count();
+// What the host-side choices need to know about the current device, asked of the runtime once
+// per device: compute units, LDS per compute unit, and the size of the last-level cache (the
+// largest cache the HSA runtime lists for the agent; the L2 size HIP reports if that fails).
+// With no GPU in the process: 256 units, 160 KiB, 256 MiB (MI355X).
+struct DeviceInfo {
+    int cus;
+    int64_t lds_bytes;
+    int64_t llc_bytes;
+};
+constexpr int kMaxDevices = 64;
+int current_device();                 // ordinal of the current HIP device, 0 if there is none
+const DeviceInfo& device_info();
+inline int device_cu_count() { return device_info().cus; }
+
+// A value remembered per device (kernel attributes set, occupancy queried): 0 = not yet known.
+// Racing first calls compute the same value twice, which is harmless.
+struct PerDeviceInt {
+    std::atomic<int> v[kMaxDevices];
+    int get() const { return v[current_device()].load(std::memory_order_relaxed); }
+    void set(int x) { v[current_device()].store(x, std::memory_order_relaxed); }
+};
 
 // ---------------------------------------------------------------- problem geometry
 //
@@ -107,8 +128,8 @@ fk_status launch_round_centroids(const Geometry& g, const float* C_f32, void* C_
 // Fused distance + online argmin.  16-bit: reads c_frag/c_bias; fp32: reads C directly.
 fk_status launch_assign(const Geometry& g, const void* X, const void* C_or_frag,
                         const float* c_bias, int32_t* assign, float* min_dist, hipStream_t s);
-// Tile shape the sweeping assign kernel would use for this many points (see fk_assign.hip).
-int choose_assign_variant(int64_t total_points);
+// Tile shape the sweeping assign kernel would use for this problem (see fk_assign.hip).
+int choose_assign_variant(const Geometry& g);
 void set_assign_variant_override(int v);   // -1 = choose from the shape
 // Few centroids: persistent streaming kernel instead of the sweeping one (see fk_assign.hip).
 bool assign_uses_stream_kernel(const Geometry& g);

@@ -280,13 +280,13 @@ __global__ __launch_bounds__(WAVES * 64) void stream_update_kernel(
 }
 
 // ------------------------------------------------------------------------------------
-static int g_fused_option = -1;   // -1 / 1: use when the shape allows, 0: never
+static std::atomic<int> g_fused_option{-1};   // -1 / 1: use when the shape allows, 0: never
 
-void set_fused_update_option(int v) { g_fused_option = v; }
+void set_fused_update_option(int v) { g_fused_option.store(v, std::memory_order_relaxed); }
 
-bool fused_update_allowed() { return g_fused_option != 0; }
+bool fused_update_allowed() { return g_fused_option.load(std::memory_order_relaxed) != 0; }
 
-bool fused_update_enabled(const Geometry& g) { return g.fused_grid_cap > 0 && g_fused_option != 0; }
+bool fused_update_enabled(const Geometry& g) { return g.fused_grid_cap > 0 && fused_update_allowed(); }
 
 template <bool BF, int DCH, bool ASSIGN>
 static fk_status launch_stream_update_t(const Geometry& g, const Workspace& w, const void* X,
@@ -294,17 +294,17 @@ static fk_status launch_stream_update_t(const Geometry& g, const Workspace& w, c
     constexpr int WAVES = 4;
     auto kern = stream_update_kernel<BF, DCH, WAVES, ASSIGN>;
     const size_t lds = (size_t)WAVES * 3 * (DCH * 64 + (ASSIGN ? 0 : 16)) * 16;
-    // queried once per kernel: the launch path stays free of runtime queries afterwards
-    static int per_cu = 0;
-    if (per_cu == 0) {
+    // set / queried once per kernel and device: the launch path stays free of runtime queries afterwards
+    static PerDeviceInt per_cu;
+    if (per_cu.get() == 0) {
         FK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         int q = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&q, kern, WAVES * 64, lds) != hipSuccess || q < 1)
             q = 1;
-        per_cu = q;
+        per_cu.set(q);
     }
     const int64_t nbatches = cdiv(g.N, 32);
-    int64_t G = cdiv((int64_t)device_cu_count() * per_cu, g.B);
+    int64_t G = cdiv((int64_t)device_cu_count() * per_cu.get(), g.B);
     G = std::min<int64_t>(G, g.fused_grid_cap);
     G = std::min<int64_t>(G, cdiv(nbatches, WAVES));
     G = std::max<int64_t>(G, 1);

@@ -485,9 +485,9 @@ static int ceil_log2(int v) {
 }
 
 // upper limit of the LDS-staged scatter, in bins (fk_set_option("sort_stage_bins"); 0 = never)
-static int g_stage_max_bins = 1024;
+static std::atomic<int> g_stage_max_bins{1024};
 
-void set_sort_stage_bins(int v) { g_stage_max_bins = v < 0 ? 1024 : v; }
+void set_sort_stage_bins(int v) { g_stage_max_bins.store(v < 0 ? 1024 : v, std::memory_order_relaxed); }
 
 static fk_status sort_pass(const Geometry& g, const Workspace& w, const int32_t* keys,
                            const int32_t* vals_in, int32_t* vals_out, int32_t* keys_out,
@@ -523,14 +523,14 @@ static fk_status sort_pass(const Geometry& g, const Workspace& w, const int32_t*
     // (2^20 .. 2^25 keys): pays from 32 bins (below that a wave's stores already fall into few
     // runs) up to 1024 (beyond, the LDS footprint costs more than the runs, 1-2 keys, give);
     // 2x on the 64..256-bin passes of the two-pass sort.
-    const int staged = rounds == 1 && NB >= 32 && NB <= g_stage_max_bins ? 1 : 0;
+    const int staged = rounds == 1 && NB >= 32 && NB <= g_stage_max_bins.load(std::memory_order_relaxed) ? 1 : 0;
     const size_t lds = (size_t)(NB + 40 + waves * NB + (staged ? NB + 2 * kSubTile : 0)) * sizeof(int);
     if (lds > 64 * 1024) {
-        static bool attr_set[2] = {false, false};
-        if (!attr_set[wide]) {
+        static PerDeviceInt attr_set[2];
+        if (!attr_set[wide].get()) {
             FK_HIP(hipFuncSetAttribute(wide ? (const void*)sort_scatter_kernel<4> : (const void*)sort_scatter_kernel<8>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));
-            attr_set[wide] = true;
+            attr_set[wide].set(1);
         }
     }
     if (wide)

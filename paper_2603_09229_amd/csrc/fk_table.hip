@@ -280,13 +280,13 @@ static fk_status launch_table_update_t(const Geometry& g, const Workspace& w, co
     auto kern = table_update_kernel<BF, DCH>;
     const size_t lds = (size_t)g.ktiles * DCH * 1024 + (size_t)256 * g.d * 2 + (size_t)g.ktiles * 128 +
                        256 * 4 + 8 * (256 + 32) * 4;
-    static bool attr_set = false;
-    if (!attr_set) {
-        FK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        attr_set = true;
+    static PerDeviceInt attr_set;
+    if (!attr_set.get()) {
+        FK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)device_info().lds_bytes));
+        attr_set.set(1);
     }
-    if (lds > 160 * 1024) {
-        set_error("table update: %zu bytes of LDS needed, 160 KiB available", lds);
+    if ((int64_t)lds > device_info().lds_bytes) {
+        set_error("table update: %zu bytes of LDS needed, %lld available", lds, (long long)device_info().lds_bytes);
         return FK_EUNSUPPORTED;
     }
     // one persistent workgroup per compute unit, shared out over the instances

@@ -38,7 +38,7 @@ def test_library_host_code_under_address_and_undefined_behaviour_sanitizers(tmp_
     san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
            "-Xarch_host", "-fno-sanitize-recover=all", "-Xarch_host", "-fno-omit-frame-pointer"]
     flags = [f for f in fk_build.FLAGS if f != "-O3"]
-    cmd = [fk_build.HIPCC, *flags, "-O1", "-g", *san, "-shared-libsan", "-o", str(lib), *map(str, fk_build.sources())]
+    cmd = [fk_build.HIPCC, *flags, "-O1", "-g", *san, "-shared-libsan", "-o", str(lib), *map(str, fk_build.sources()), *fk_build.LIBS]
     r = subprocess.run(cmd, capture_output=True, text=True)
     assert r.returncode == 0, r.stderr[-3000:]
     exe = tmp_path / "api_san"
