@@ -85,8 +85,11 @@ def test_plan_describes_the_choice_per_shape():
     assert "mfma_sweep(variant=0" in fk.fk_plan(1, 300000, 128, 1024, f16)      # least idle last round
     assert "mfma_stream" in fk.fk_plan(1, 1 << 24, 64, 16, f16)             # X far beyond the cache
     assert "mfma_sweep" in fk.fk_plan(1, 1 << 20, 64, 16, f16)              # X cache-sized: bulk loads
-    assert "mfma_stream" in fk.fk_plan(1, 1 << 24, 64, 100, f16)            # still one LDS stage at d = 64
-    assert "mfma_sweep" in fk.fk_plan(1, 1 << 24, 128, 100, f16)            # more than a stage at d = 128
+    assert "mfma_stream" in fk.fk_plan(1, 1 << 24, 64, 64, f16)             # two centroid tiles: still streaming
+    assert "mfma_sweep(variant=0" in fk.fk_plan(1, 1 << 24, 64, 100, f16)   # more: sweeping, HBM-bound shape
+    assert "mfma_sweep" in fk.fk_plan(1, 1 << 24, 128, 100, f16)
+    assert "mfma_sweep(variant=2" in fk.fk_plan(1, 1 << 19, 64, 100, f16)   # same K with X inside the last-level cache
+    assert "device(cus=256,lds=160KiB,llc=256MiB)" in fk.fk_plan(1, 1000, 64, 8, f16)   # no GPU: MI355X figures
     assert "mfma_sweep" in fk.fk_plan(1, 1 << 25, 32, 16, f16)              # narrow rows
     assert "mfma_wide(chunks=32" in fk.fk_plan(1, 1 << 20, 512, 65536, f16)
     assert "sort=2pass" in fk.fk_plan(1, 1 << 20, 512, 65536, f16)
