@@ -4,6 +4,7 @@
     python -m paper_2603_09229_amd.profile_summary traffic <fetch_dir> <write_dir> <kernel substring> <kernel name> <workload> <out.txt> "<command>"
     python -m paper_2603_09229_amd.profile_summary counters <dir1> <dir2> <kernel substring> <out.txt> "<command 1>" "<command 2>"
     python -m paper_2603_09229_amd.profile_summary ooc-overlap <dir> <out.txt> "<command>"
+    python -m paper_2603_09229_amd.profile_summary bench-json <bench output.json> <out.txt> "<command>" "<title>"
 
 The raw output (CSV files, databases) stays where rocprofv3 wrote it; only the summary is meant
 to be committed.  Every summary starts with the command that produced its input.
@@ -197,6 +198,31 @@ def ooc_overlap(dirname: str, out: str, command: str) -> None:
     print(open(out).read())
 
 
+def bench_json(json_file: str, out: str, command: str, title: str) -> None:
+    """One JSON line printed by bench.py (a run, a sweep, a comparison) as readable text: scalars
+    one per line, every list of records one record per line."""
+    import json
+    d = json.loads(open(json_file).read().strip().splitlines()[-1])
+
+    def emit(o, key, val, indent=""):
+        if isinstance(val, list) and val and isinstance(val[0], dict):
+            o.write(f"{indent}{key}:\n")
+            for r in val:
+                o.write(f"{indent}  " + json.dumps(r, separators=(", ", ": ")) + "\n")
+        elif isinstance(val, dict) and any(isinstance(v, (dict, list)) for v in val.values()):
+            o.write(f"{indent}{key}:\n")
+            for k, v in val.items():
+                emit(o, k, v, indent + "  ")
+        else:
+            o.write(f"{indent}{key}: " + (json.dumps(val, separators=(", ", ": ")) if isinstance(val, (dict, list)) else str(val)) + "\n")
+
+    with open(out, "w") as o:
+        o.write(f"{title} (one MI355X)\n")
+        o.write(f"command: {command}\n")
+        for k, v in d.items():
+            emit(o, k, v)
+
+
 def main(argv) -> int:
     if len(argv) < 2:
         print(__doc__)
@@ -210,6 +236,8 @@ def main(argv) -> int:
         counters(*a)
     elif mode == "ooc-overlap":
         ooc_overlap(*a)
+    elif mode == "bench-json":
+        bench_json(*a)
     else:
         print(__doc__)
         return 2
