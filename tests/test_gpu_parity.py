@@ -550,7 +550,7 @@ def test_standard_comparator_update(dtype, B, N, d, K):
 
 
 @pytest.mark.parametrize("dtype,N,d,K", [(torch.float16, 30000, 128, 300), (torch.float16, 40000, 64, 16),
-                                         (torch.float32, 5000, 64, 20)])
+                                         (torch.float32, 5000, 64, 20), (torch.bfloat16, 30000, 128, 200)])
 def test_iteration_replays_from_a_hip_graph(dtype, N, d, K):
     """The library allocates nothing and enqueues kernels only, so one iteration can be captured
     into a graph and replayed.  Replays are interleaved with eager work and each is compared
