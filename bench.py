@@ -65,7 +65,9 @@ def main() -> int:
                          "direct scatter in the counting sort (prints one JSON line)")
     ap.add_argument("--clock-trace", action="store_true",
                     help="loop the assign kernel (and a device copy) for a few seconds each while "
-                         "sampling the shader clock with rocm-smi (prints one JSON line)")
+                         "sampling the shader clock with rocm-smi; also times the headline shape "
+                         "on operands that toggle less (zeros, ones) to show what the power limit "
+                         "costs (prints one JSON line)")
     ap.add_argument("--general-update", action="store_true",
                     help="few-cluster shapes: use the general assign + sort-inverse path instead "
                          "of the fused one-hot pass (for comparing the two)")
@@ -379,6 +381,29 @@ def clock_trace(torch, fk, dev):
 
     N, d = 1 << 20, 128
     X = (torch.randn(1, N, d, device=dev) * 4).half()
+    # The headline shape (same instructions, same schedule) on operands that toggle the
+    # multipliers less: what the instruction stream sustains with the power limit out of the way.
+    # Timed before the first rocm-smi call (median of three interleaved rounds); the clocks under
+    # each are sampled further down.
+    Kp = 1024
+    ws_p = fk.make_workspace(1, N, d, Kp, torch.float16, dev)
+    a_p = torch.empty((1, N), dtype=torch.int32, device=dev)
+    Cp = (torch.randn(1, Kp, d, device=dev) * 4).half()
+    probe = [{"operands": name, "_ops": ops} for name, ops in (
+        ("gaussian X, gaussian C", (X, Cp)),
+        ("all-zero X and C", (torch.zeros_like(X), torch.zeros_like(Cp))),
+        ("all-one X and C", (torch.ones_like(X), torch.ones_like(Cp))),
+        ("gaussian X, all-zero C", (X, torch.zeros_like(Cp))))]
+    t0 = time.time()
+    while time.time() - t0 < 0.3:
+        fk.fk_assign(X, Cp, ws=ws_p, out=a_p)
+    torch.cuda.synchronize()
+    rounds = [[_time_us(torch, lambda: fk.fk_assign(*row["_ops"], ws=ws_p, out=a_p), reps=40) for row in probe]
+              for _ in range(3)]
+    for i, row in enumerate(probe):
+        us = sorted(r[i] for r in rounds)[1]
+        row["us_per_call_incl_centroid_layout"] = us
+        row["tflops"] = 2.0 * N * Kp * d / us / 1e6
     out = {"metric": "shader_clock_under_load_mhz", "idle": sclk(), "loads": []}
     for K in (16384, 1024, 256):
         C = (torch.randn(1, K, d, device=dev) * 4).half()
@@ -387,6 +412,10 @@ def clock_trace(torch, fk, dev):
         us = _time_us(torch, lambda: fk.fk_assign(X, C, ws=ws, out=a))
         out["loads"].append({"load": f"fk_assign N=2^20 d=128 K={K} fp16", "sclk_mhz": loop(lambda: fk.fk_assign(X, C, ws=ws, out=a)),
                              "tflops": 2.0 * N * K * d / us / 1e6})
+    for row in probe:
+        Xo, Co = row.pop("_ops")
+        row["sclk_mhz"] = loop(lambda: fk.fk_assign(Xo, Co, ws=ws_p, out=a_p), secs=2.0)
+    out["operand_data"] = probe
     src = torch.empty(1 << 28, dtype=torch.float32, device=dev)
     dst = torch.empty_like(src)
     out["loads"].append({"load": "1 GiB device-to-device copy", "sclk_mhz": loop(lambda: dst.copy_(src))})
