@@ -207,7 +207,7 @@ def measure(w, steps, warmup, repeats, torch, fk, wl, dev, cpu=True):
     es = 4 if w.dtype == "fp32" else 2
     flops = 2.0 * w.B * w.N * w.K * w.d
     plan = fk.fk_plan(w.B, w.N, w.d, w.K, w.torch_dtype)
-    fused = "stream_update" in plan or "table_update" in plan
+    fused = any(k in plan for k in ("stream_update", "table_update", "f32_update"))
     out = {
         "metric": "lloyd_iterations_per_s",
         "value": 1e3 / ms_per_step,
@@ -228,7 +228,16 @@ def measure(w, steps, warmup, repeats, torch, fk, wl, dev, cpu=True):
         "prewarm_iterations_untimed": prewarm,
     }
     pass_bytes = w.B * (w.N * w.d * es + w.K * w.d * es + 4 * w.K + 4 * w.N)
-    if fused:
+    if fused and "f32_update" in plan:
+        # fp32 storage, few clusters: the same one-pass structure, distances by direct differences
+        # on the fp32 vector ALU (3 flop per point, centroid and feature): ALU-bound
+        out["config"]["update"] = "fused into the assignment pass (fp32 table in registers)"
+        t = 1.5 * flops / (kernel["assign"] * 1e-3) / 1e12
+        out["assign_tflops"] = flops / (kernel["assign"] * 1e-3) / 1e12
+        out["fused_pass_gbps"] = pass_bytes / (kernel["assign"] * 1e-3) / 1e9
+        out["roofline"] = _roof("f32_update_kernel", "alu", t, PEAK_FP32_VALU_TFLOPS, "TFLOP/s", w,
+                                kernel["assign"], interval["assign"])
+    elif fused:
         # assignment and sums come out of ONE streaming pass over X (booked under "assign"; no
         # sort, no gather), followed by the merge/normalise.  HBM-bound: X and C read once, the
         # assignment written once.

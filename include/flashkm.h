@@ -222,7 +222,7 @@ fk_status fk_standard_update(const void* X, const int32_t* assign, const float* 
  *                        when a pass has 32..n bins (default 1024; 0 = never)
  *   "sort_min_rounds" r  sort workgroups own at least r sub-tiles of 4096 keys (the rule gives
  *                        one up to 2^24 keys); changes fk_workspace_bytes, so set it before sizing
- *   "fused_update"   0   do not take the sort-free one-pass updates below (K <= 256)
+ *   "fused_update"   0   do not take the sort-free one-pass updates below
  *   "timer_repeat"   r   measurement only: while the stage timer runs, the assignment (or fused)
  *                        kernel and the segment reduction are each launched r times back to back
  *                        inside their interval (same outputs rewritten), so that interval /
@@ -237,8 +237,14 @@ fk_status fk_standard_update(const void* X, const int32_t* assign, const float* 
  * in the accumulators of its eight waves (32 clusters each) and adds the points it has just
  * assigned, compacted per wave, with a one-hot MFMA.  Same assignments and counts as the general
  * path, sums up to fp32 summation order, bit-reproducible.  fk_update alone keeps the
- * sort-inverse path for these shapes.  Both passes need room for one partial table per
- * workgroup, which fk_workspace_bytes includes.
+ * sort-inverse path for these shapes.
+ * Small fp32 problems (FK_F32, K <= 64, d <= 128, B*N <= 2^17): fk_lloyd_iter likewise takes one
+ * pass per iteration (64-point batches, distances by the same fp32 differences as fk_assign, each
+ * cluster's row of the table of sums owned by one wave): at this size the iteration is bound by
+ * its number of launches.  Same assignments and counts as the general path, sums up to fp32
+ * summation order, bit-reproducible; fk_update alone keeps the sort-inverse path.
+ * All of these passes need room for one partial table per workgroup, which fk_workspace_bytes
+ * includes.
  */
 int fk_plan(int B, int64_t N, int d, int K, fk_dtype t, char* buf, size_t buf_bytes);
 int fk_set_option(const char* name, int value);

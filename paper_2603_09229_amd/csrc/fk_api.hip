@@ -124,6 +124,12 @@ bool make_geometry(int B, int64_t N, int d_user, int K, fk_dtype t, Geometry* g)
     g->table_grid_cap = 0;
     if (t != FK_F32 && K > 32 && K <= 256 && d <= 128)
         g->table_grid_cap = (int)std::min<int64_t>(B >= 256 ? 1 : 256 / B, cdiv(N, 256));
+    // small fp32 problems (at most 2^17 points in all, where the iteration is bound by its
+    // number of launches: measured 1.5x at 2^14 points, break-even near 2^18): 64-point batches,
+    // up to 2048 workgroups in all
+    g->f32_grid_cap = 0;
+    if (t == FK_F32 && K <= 64 && d <= 128 && (int64_t)B * N <= ((int64_t)1 << 17))
+        g->f32_grid_cap = (int)std::min<int64_t>(B >= 2048 ? 1 : 2048 / B, cdiv(N, 64));
     return true;
 }
 
@@ -159,7 +165,7 @@ Workspace carve(const Geometry& g, void* base, bool padded_x) {
         w.c_frag = take((size_t)g.B * g.ktiles * g.dchunks * 64 * 16);
         w.c_bias = (float*)take((size_t)g.B * g.ktiles * 32 * 4);
     }
-    const size_t fused_rows = (size_t)g.K * std::max(g.fused_grid_cap, g.table_grid_cap);
+    const size_t fused_rows = (size_t)g.K * std::max({g.fused_grid_cap, g.table_grid_cap, g.f32_grid_cap});
     w.partial = (float*)take((size_t)g.B * std::max((size_t)g.max_items, fused_rows) * g.d * 4);
     if (fused_rows > 0) w.wg_counts = (int32_t*)take((size_t)g.B * fused_rows * 4);
     w.sums = (float*)take(BKd * 4);
@@ -309,8 +315,10 @@ static fk_status run_stream_update(const Geometry& g, const Workspace& w, const 
     for (int r = 0; r < rep; ++r) {
         if (g.fused_grid_cap > 0)
             FK_TRY(launch_stream_update(g, w, X, assign, compute_assign, &G, s));
-        else
+        else if (g.table_grid_cap > 0)
             FK_TRY(launch_table_update(g, w, X, assign, &G, s));    // always computes the assignment
+        else
+            FK_TRY(launch_f32_update(g, w, X, fa.C_prev_f32, assign, &G, s));   // likewise
     }
     timer_mark(s, compute_assign ? kStageAssign : kStageReduce, rep);
     Geometry gm = g;
@@ -471,6 +479,12 @@ int fk_plan(int B, int64_t N, int d, int K, fk_dtype t, char* buf, size_t buf_by
                  "assign+update=stream_update(one-hot MFMA, X read once per iteration, no sort; "
                  "at most %d workgroups per instance) fk_assign alone=%s workspace=%zu",
                  g.fused_grid_cap, assign, carve(g, nullptr).bytes);
+    } else if (f32_update_enabled(g)) {
+        snprintf(buf, buf_bytes,
+                 "assign+update=f32_update(K x d table in the registers of a workgroup, X read once "
+                 "per iteration, no sort; at most %d workgroups per instance) fk_assign alone=%s "
+                 "fk_update alone=sort-inverse workspace=%zu",
+                 g.f32_grid_cap, assign, carve(g, nullptr).bytes);
     } else {
         snprintf(buf, buf_bytes,
                  "assign=%s ktiles=%d sort=%dpass(tile=%d,blocks=%d) reduce=%s(rows_per_item=%d) "
@@ -707,7 +721,7 @@ fk_status fk_lloyd_iter(const void* X, float* C_f32, void* C_lp, int32_t* assign
     for (int it = 0; it < iters; ++it) {
         timer_mark(s, -1);
         // few clusters: assignment and sums in one pass over X (see run_stream_update)
-        const bool fused = fused_update_enabled(g) || table_update_enabled(g);
+        const bool fused = fused_update_enabled(g) || table_update_enabled(g) || f32_update_enabled(g);
         if (!fused) {
             const int rep = timer_repeat();
             for (int r = 0; r < rep; ++r) {

@@ -87,6 +87,9 @@ struct Geometry {
     // one-pass update with the K x d table split over the registers of a workgroup (16-bit
     // storage, 32 < K <= 256, d <= 128): most workgroups per instance, 0 when not eligible
     int table_grid_cap;
+    // one-pass assignment + sums for small fp32 problems (K <= 64, d <= 128, at most 2^17 points
+    // in all; see fk_f32_fused.hip): most workgroups per instance, 0 when not eligible
+    int f32_grid_cap;
 };
 
 // Carved device workspace (all pointers 256-byte aligned inside the caller's buffer).
@@ -102,8 +105,8 @@ struct Workspace {
     int32_t* keys_tmp;   // [B,N] keys after pass 1 (two-pass sort only)
     int32_t* vals_tmp;   // [B,N] values after pass 1 (two-pass sort only)
     int32_t* keys_sorted;// [B,N] sorted keys (two-pass sort only)
-    float* partial;      // [B,max(max_items, K*fused_grid_cap),d] per-item segment sums
-    int32_t* wg_counts;  // [B,K,fused_grid_cap] per-workgroup counts (few-cluster update only)
+    float* partial;      // [B,max(max_items, K*(largest one-pass grid cap)),d] per-item segment sums
+    int32_t* wg_counts;  // [B,K,grid cap] per-workgroup counts (one-pass updates only)
     float* sums;         // [B,K,d] accumulated sums (chunked mode)
     void* x_pad;         // [B,N,d] zero-padded copy of X            (only when d != d_user)
     float* c_pad_f32;    // [B,K,d] zero-padded fp32 centroids       (only when d != d_user)
@@ -180,6 +183,13 @@ bool fused_update_allowed();               // the option above is not 0
 fk_status launch_table_update(const Geometry& g, const Workspace& w, const void* X,
                               int32_t* assign, int* grid_out, hipStream_t s);
 bool table_update_enabled(const Geometry& g);
+
+// Small fp32 problems, up to 64 clusters: assignment and sums in one pass over X (see
+// fk_f32_fused.hip).  C_f32 [B,K,d] are the centroids to assign against.  Computes and writes the
+// assignment; leaves w.partial / w.wg_counts as launch_stream_update does.
+fk_status launch_f32_update(const Geometry& g, const Workspace& w, const void* X,
+                            const float* C_f32, int32_t* assign, int* grid_out, hipStream_t s);
+bool f32_update_enabled(const Geometry& g);
 
 // Row re-layout for widths that are not a multiple of 8: dst[r][j] = j < d_src ? src[r][j] : 0
 // for j < d_dst (padding, d_dst > d_src) or dst[r][j] = src[r][j] for j < d_dst (un-padding,

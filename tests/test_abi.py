@@ -97,8 +97,16 @@ def test_plan_describes_the_choice_per_shape():
     assert "stream_update" in fk.fk_plan(1, 1 << 24, 64, 16, f16)
     assert "stream_update" not in fk.fk_plan(1, 1 << 24, 64, 16, torch.float32)
     assert "stream_update" not in fk.fk_plan(1, 1 << 24, 64, 33, f16)
+    # small fp32 problems: one pass as well; larger ones keep assign + sort-inverse
+    f32 = torch.float32
+    assert "f32_update" in fk.fk_plan(1, 16384, 64, 64, f32)
+    assert "f32_update" in fk.fk_plan(4, 32768, 128, 8, f32)
+    assert "f32_update" not in fk.fk_plan(1, (1 << 17) + 1, 64, 64, f32)
+    assert "f32_update" not in fk.fk_plan(1, 16384, 64, 65, f32)
+    assert "f32_update" not in fk.fk_plan(1, 16384, 136, 64, f32)
     fk.fk_set_option("fused_update", 0)
     assert "workgroup_per_item" in fk.fk_plan(1, 1 << 24, 64, 16, f16)
+    assert "f32_update" not in fk.fk_plan(1, 16384, 64, 64, f32)
     fk.fk_set_option("fused_update", -1)
     assert fk.fk_plan(1, 100, 600, 3, f16) == "unsupported"
     assert "rows_padded=12->16" in fk.fk_plan(1, 100, 12, 40, f16)

@@ -550,7 +550,8 @@ def test_standard_comparator_update(dtype, B, N, d, K):
 
 
 @pytest.mark.parametrize("dtype,N,d,K", [(torch.float16, 30000, 128, 300), (torch.float16, 40000, 64, 16),
-                                         (torch.float32, 5000, 64, 20), (torch.bfloat16, 30000, 128, 200)])
+                                         (torch.float32, 5000, 64, 20), (torch.float32, 5000, 64, 70),
+                                         (torch.bfloat16, 30000, 128, 200)])
 def test_iteration_replays_from_a_hip_graph(dtype, N, d, K):
     """The library allocates nothing and enqueues kernels only, so one iteration can be captured
     into a graph and replayed.  Replays are interleaved with eager work and each is compared
@@ -800,6 +801,84 @@ def test_table_update_is_bit_reproducible_and_multi_iteration():
     Cc = C0.clone()
     a3, _, _ = fk.fk_lloyd_iter(Xd, Cc, 1)
     assert torch.equal(a3, fk.fk_assign(Xd, C0.to(w.torch_dtype)))
+
+
+F32_FEW_CLUSTER_CASES = [
+    # B, N, d, K, zipf
+    (1, 16384, 64, 64, 0.0),          # the tiny fp32 benchmark shape
+    (1, 70001, 128, 64, 0.0),         # widest rows, ragged last batch, several batches per workgroup
+    (3, 1000, 40, 7, 1.2),            # d between the compiled widths, skewed, batched
+    (1, 50000, 32, 33, 0.0),
+    (2, 333, 8, 1, 0.0),              # one cluster
+    (1, 63, 24, 5, 0.0),              # less than one batch
+    (1, 1, 16, 1, 0.0),               # one point
+    (1, 90, 64, 64, 0.0),             # K about N: most clusters nearly empty
+    (1, 5000, 13, 6, 0.0),            # rows that are not a multiple of 8 wide: padded copy
+    (2100, 60, 16, 3, 0.0),           # more instances than workgroups to share: one each
+]
+
+
+@pytest.mark.parametrize("B,N,d,K,zipf", F32_FEW_CLUSTER_CASES)
+def test_f32_few_cluster_iteration_matches_oracle_and_general_path(B, N, d, K, zipf, general_path_switch):
+    """fp32 storage, K <= 64: assignment and sums in one pass; against the oracle and against
+    the general assign + sort-inverse path (identical assignments: same arithmetic)."""
+    dtype = torch.float32
+    w, X, lab, C0 = _problem(dtype, B, N, d, K, seed=900 + N + K, zipf=zipf)
+    Xd = X.to(DEV)
+    assert "f32_update" in fk.fk_plan(B, N, d, K, dtype)
+    C_f = C0.to(DEV).clone()
+    a_f, n_f, lp_f = fk.fk_lloyd_iter(Xd, C_f, 1)
+    general_path_switch(True)
+    assert "f32_update" not in fk.fk_plan(B, N, d, K, dtype)
+    C_s = C0.to(DEV).clone()
+    a_s, n_s, lp_s = fk.fk_lloyd_iter(Xd, C_s, 1)
+    general_path_switch(False)
+    torch.cuda.synchronize()
+    assert torch.equal(a_f, a_s) and torch.equal(n_f, n_s)
+    for b in range(min(B, 8)):
+        Xb = parity.widen(X[b])
+        parity.check_assign(Xb, parity.widen(C0[b]), a_f[b].cpu().numpy())
+        parity.check_update(Xb, a_f[b].cpu().numpy(), C0[b].numpy(), C_f[b].cpu().numpy(),
+                            n_f[b].cpu().numpy(), parity.CENTROID_TOL[dtype])
+    parity.check_centroids(C_f.cpu().numpy().reshape(B * K, d), C_s.cpu().numpy().reshape(B * K, d), 2e-6,
+                           "one pass vs sort-inverse")
+    assert torch.equal(lp_f.cpu(), C_f.cpu())
+
+
+def test_f32_few_cluster_path_is_bit_reproducible_and_multi_iteration():
+    dtype = torch.float32
+    w, X, lab, C0 = _problem(dtype, 2, 40000, 64, 48, seed=931)
+    Xd = X.to(DEV)
+    outs = []
+    for _ in range(2):
+        C = C0.to(DEV).clone()
+        a, n, lp = fk.fk_lloyd_iter(Xd, C, 4)
+        torch.cuda.synchronize()
+        outs.append((C.cpu(), a.cpu(), n.cpu()))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1]) and torch.equal(outs[0][2], outs[1][2])
+    # four iterations in one call = four calls of one iteration
+    C = C0.to(DEV).clone()
+    for _ in range(4):
+        a, n, lp = fk.fk_lloyd_iter(Xd, C, 1)
+    torch.cuda.synchronize()
+    assert torch.equal(C.cpu(), outs[0][0]) and torch.equal(a.cpu(), outs[0][1])
+    assert int(n.sum()) == 2 * 40000
+
+
+def test_f32_few_cluster_all_points_in_one_cluster_and_empty_clusters():
+    """Every point nearest to centroid 5: the other clusters are empty and keep their rows."""
+    torch.manual_seed(77)
+    N, d, K = 3000, 48, 20
+    X = torch.randn(1, N, d) * 0.1
+    C0 = torch.randn(1, K, d) * 50.0
+    C0[0, 5] = 0.0
+    C = C0.to(DEV).clone()
+    a, n, lp = fk.fk_lloyd_iter(X.to(DEV), C, 1)
+    torch.cuda.synchronize()
+    assert int((a != 5).sum()) == 0 and int(n[0, 5]) == N and int(n.sum()) == N
+    keep = [k for k in range(K) if k != 5]
+    assert torch.equal(C.cpu()[0, keep], C0[0, keep])
+    parity.check_centroids(C.cpu().numpy()[0, 5:6], X[0].double().mean(0, keepdim=True).numpy(), 1e-5, "mean")
 
 
 def test_kernel_choices_do_not_change_the_result():
