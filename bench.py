@@ -250,7 +250,11 @@ def measure(w, steps, warmup, repeats, torch, fk, wl, dev, cpu=True):
     else:
         assign_tflops = flops / (kernel["assign"] * 1e-3) / 1e12
         upd_bytes = w.B * (w.N * (w.d * es + 12) + w.K * w.d * (4 + es))
-        upd_ms = kernel["sort"] + kernel["reduce"] + kernel["finalize"]
+        # the update's share of an iteration: the timed iteration minus the assignment kernel's own
+        # duration (everything else, launch gaps included); the sum of the stage intervals, which
+        # also holds one event pair per stage, is kept beside it
+        upd_ms = ms_per_step - kernel["assign"]
+        upd_ms_stages = kernel["sort"] + kernel["reduce"] + kernel["finalize"]
         update_gbps = upd_bytes / (upd_ms * 1e-3) / 1e9
         out.update({
             "assign_tflops": assign_tflops,
@@ -259,6 +263,7 @@ def measure(w, steps, warmup, repeats, torch, fk, wl, dev, cpu=True):
             "update_gbps": update_gbps,
             "update_frac_of_hbm_peak": update_gbps / PEAK_HBM_GBPS,
             "update_ms": upd_ms,
+            "update_ms_sum_of_stage_intervals": upd_ms_stages,
         })
         # dominant kernel: the assignment kernel wherever its contraction outweighs streaming X
         # (K above the MFMA/HBM ridge of ~312 flop/byte); otherwise the update's row gather
@@ -288,11 +293,13 @@ def _roof(kname, bound, achieved, peak, unit, w, kernel_ms, interval_ms):
     (back-to-back launches between one event pair, live in this run); the single-launch event
     interval, which also holds the events' own cost, is kept beside it.  `traffic` is not measured
     in this run: it is the figure of the committed rocprofv3 --pmc summary, when there is one."""
+    traffic = _traffic_from_profiles(kname, w.name)
     return {"kernel": kname, "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
             "frac": achieved / peak, "avg_launch_ms": kernel_ms,
             "avg_launch_ms_single_event_interval": interval_ms,
-            "traffic": _traffic_from_profiles(kname, w.name),
-            "traffic_source": f"profiles/{kname}_{w.name}_traffic.txt (offline rocprofv3 --pmc run)"}
+            "traffic": traffic,
+            "traffic_source": (f"profiles/{kname}_{w.name}_traffic.txt (offline rocprofv3 --pmc run)"
+                               if traffic is not None else None)}
 
 
 def _time_us(torch, fn, reps=5):
